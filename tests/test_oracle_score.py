@@ -1,0 +1,202 @@
+"""Pins of the scoring oracle (CPU only): brute force, library softmax, closed
+forms, invariants and planted heavy hitters.  None of these re-uses the oracle's
+own formula; each is chosen so that a dropped term, a wrong mask, scale or
+reduction axis fails at least one of them."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_16360_amd import synth
+
+
+def _rand(shape, seed):
+    g = torch.Generator().manual_seed(seed)
+    return torch.randn(*shape, generator=g, dtype=torch.float64)
+
+
+def _brute_rows(q, k_ctx, k_rec, chunk):
+    """Per-row Python loops with math.exp: query i sees all context keys and
+    reconstruction keys j of its own chunk with j <= i."""
+    N_q, d = q.shape
+    N = k_ctx.shape[0]
+    P = np.zeros((N_q, N))
+    R = np.zeros((N_q, N_q))
+    for i in range(N_q):
+        logits = [float(np.dot(q[i], k_ctx[n])) / math.sqrt(d) for n in range(N)]
+        lo = (i // chunk) * chunk
+        rec = [float(np.dot(q[i], k_rec[j])) / math.sqrt(d) for j in range(lo, i + 1)]
+        top = max(logits + rec)
+        Z = sum(math.exp(v - top) for v in logits) + sum(math.exp(v - top) for v in rec)
+        for n in range(N):
+            P[i, n] = math.exp(logits[n] - top) / Z
+        for jj, j in enumerate(range(lo, i + 1)):
+            R[i, j] = math.exp(rec[jj] - top) / Z
+    return P, R
+
+
+@pytest.mark.parametrize("G,N,N_q,chunk,d", [(1, 7, 5, 5, 4), (2, 13, 10, 4, 8), (3, 9, 7, 3, 2)])
+def test_score_unit_matches_brute_force(G, N, N_q, chunk, d):
+    q, kc, kr = _rand((G, N_q, d), 1), _rand((N, d), 2), _rand((N_q, d), 3)
+    X = oracle.score_unit(q, kc, kr, chunk)
+    ref = np.zeros(N)
+    for g in range(G):
+        P, _ = _brute_rows(q[g].numpy(), kc.numpy(), kr.numpy(), chunk)
+        ref = np.maximum(ref, P.max(axis=0))
+    np.testing.assert_allclose(X.numpy(), ref, rtol=1e-12, atol=1e-15)
+    Xs = oracle.score_unit(q, kc, kr, chunk, reduce="sum")
+    ref_s = sum(_brute_rows(q[g].numpy(), kc.numpy(), kr.numpy(), chunk)[0].sum(axis=0) for g in range(G))
+    np.testing.assert_allclose(Xs.numpy(), ref_s, rtol=1e-12)
+
+
+def test_softmax_rows_match_library_softmax_on_masked_matrix():
+    N, N_q, chunk, d = 11, 9, 4, 8
+    q, kc, kr = _rand((N_q, d), 4), _rand((N, d), 5), _rand((N_q, d), 6)
+    logits = torch.cat([q @ kc.T, q @ kr.T], dim=1) / math.sqrt(d)
+    mask = torch.zeros(N_q, N + N_q, dtype=torch.bool)
+    mask[:, :N] = True
+    for i in range(N_q):
+        for j in range(N_q):
+            mask[i, N + j] = (j <= i) and (j // chunk == i // chunk)
+    lib = torch.softmax(logits.masked_fill(~mask, -math.inf), dim=1)
+    P, R = oracle.softmax_rows_unit(q, kc, kr, chunk)
+    torch.testing.assert_close(P, lib[:, :N], rtol=1e-12, atol=1e-15)
+    torch.testing.assert_close(R, lib[:, N:], rtol=1e-12, atol=1e-15)
+    # earlier chunks and the future are invisible
+    assert float(R[5, 3]) == 0.0 and float(R[5, 6]) == 0.0 and float(R[5, 4]) > 0.0 and float(R[5, 5]) > 0.0
+    X = oracle.score_unit(q[None], kc, kr, chunk)
+    torch.testing.assert_close(X, lib[:, :N].max(dim=0).values, rtol=1e-12, atol=1e-15)
+
+
+def test_rows_sum_to_one_and_scores_in_unit_interval():
+    N, N_q, chunk, d, G = 40, 24, 8, 16, 2
+    q, kc, kr = 2.0 * _rand((G, N_q, d), 7), _rand((N, d), 8), _rand((N_q, d), 9)
+    total_mass = torch.zeros(N, dtype=torch.float64)
+    for g in range(G):
+        P, R = oracle.softmax_rows_unit(q[g], kc, kr, chunk)
+        torch.testing.assert_close(P.sum(1) + R.sum(1), torch.ones(N_q, dtype=torch.float64), rtol=1e-12, atol=0)
+        total_mass += P.sum(0)
+    X = oracle.score_unit(q, kc, kr, chunk)
+    assert float(X.min()) >= 0.0 and float(X.max()) <= 1.0
+    # a maximum dominates the mean over the same (head, query) set
+    assert bool((X >= total_mass / (G * N_q) - 1e-15).all())
+    # the sum form is exactly the accumulated mass
+    torch.testing.assert_close(oracle.score_unit(q, kc, kr, chunk, reduce="sum"), total_mass, rtol=1e-12, atol=0)
+
+
+def test_uniform_rows_closed_form():
+    """Zero queries make every row uniform; the first query of a chunk sees N+1 keys,
+    so the maximum over queries is exactly 1/(N+1)."""
+    N, N_q, chunk, d = 37, 12, 5, 8
+    kc, kr = _rand((N, d), 10), _rand((N_q, d), 11)
+    X = oracle.score_unit(torch.zeros(1, N_q, d, dtype=torch.float64), kc, kr, chunk)
+    torch.testing.assert_close(X, torch.full((N,), 1.0 / (N + 1), dtype=torch.float64), rtol=1e-14, atol=0)
+    # identical keys give the same result whatever the queries are
+    same = torch.ones(N, d, dtype=torch.float64)
+    X2 = oracle.score_unit(_rand((1, N_q, d), 12), same, torch.ones(N_q, d, dtype=torch.float64), chunk)
+    torch.testing.assert_close(X2, torch.full((N,), 1.0 / (N + 1), dtype=torch.float64), rtol=1e-12, atol=0)
+
+
+def test_single_query_is_textbook_softmax_with_sqrt_d_scale():
+    d, N = 16, 6
+    q, kc, kr = _rand((1, 1, d), 13), _rand((N, d), 14), _rand((1, d), 15)
+    logits = [float(q[0, 0] @ kc[n]) / 4.0 for n in range(N)] + [float(q[0, 0] @ kr[0]) / 4.0]
+    Z = sum(math.exp(v) for v in logits)
+    ref = torch.tensor([math.exp(v) / Z for v in logits[:N]], dtype=torch.float64)
+    torch.testing.assert_close(oracle.score_unit(q, kc, kr, 1), ref, rtol=1e-12, atol=0)
+    # two-key hand case: one context key, one own key
+    p = oracle.score_unit(q, kc[:1], kr, 1)
+    a, b = float(q[0, 0] @ kc[0]) / 4.0, float(q[0, 0] @ kr[0]) / 4.0
+    assert abs(float(p[0]) - 1.0 / (1.0 + math.exp(b - a))) < 1e-14
+
+
+def test_group_max_equals_max_of_separately_scored_heads_and_gqa_mapping():
+    L, H_q, H_kv, N, N_q, chunk, d = 2, 6, 2, 17, 8, 4, 8
+    q, kc, kr = _rand((L, H_q, N_q, d), 16), _rand((L, H_kv, N, d), 17), _rand((L, H_kv, N_q, d), 18)
+    X = oracle.score(q, kc, kr, chunk, round_inputs=False)
+    assert X.shape == (L, H_kv, N)
+    G = H_q // H_kv
+    for l in range(L):
+        for h in range(H_kv):
+            sep = torch.stack([oracle.score_unit(q[l, h * G + g][None], kc[l, h], kr[l, h], chunk) for g in range(G)])
+            torch.testing.assert_close(X[l, h], sep.max(0).values, rtol=0, atol=0)
+
+
+def test_key_permutation_equivariance_and_chunk_isolation():
+    N, N_q, chunk, d = 23, 12, 4, 8
+    q, kc, kr = _rand((2, N_q, d), 19), _rand((N, d), 20), _rand((N_q, d), 21)
+    perm = torch.randperm(N, generator=torch.Generator().manual_seed(5))
+    X = oracle.score_unit(q, kc, kr, chunk)
+    torch.testing.assert_close(oracle.score_unit(q, kc[perm], kr, chunk), X[perm], rtol=1e-13, atol=0)
+    # with one chunk only (chunk >= N_q) the result differs: chunking matters
+    assert not torch.allclose(oracle.score_unit(q, kc, kr, N_q), X, rtol=1e-6, atol=0)
+    # changing the queries of chunk 0 cannot lower any score below what chunks 1.. alone give
+    alone = oracle.score_unit(q[:, chunk:], kc, kr[chunk:], chunk)
+    assert bool((X >= alone - 1e-15).all())
+
+
+def test_bf16_rounding_of_inputs():
+    x = torch.tensor([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -9, -(1.0 + 2.0 ** -7 + 2.0 ** -8), 3.0e-5],
+                     dtype=torch.float64)
+    r = oracle.round_bf16(x)
+    # ties go to the even mantissa; 8 significant bits are kept
+    assert r[0].item() == 1.0 and r[1].item() == 1.0 + 2.0 ** -6 and r[2].item() == 1.0
+    assert r[3].item() == -(1.0 + 2.0 ** -6)
+    m, e = math.frexp(r[4].item())
+    assert (m * 256) == int(m * 256)
+    q, kc, kr = _rand((1, 2, 4, 8), 22), _rand((1, 1, 9, 8), 23), _rand((1, 1, 4, 8), 24)
+    a = oracle.score(q, kc, kr, 2)
+    b = oracle.score(oracle.round_bf16(q), oracle.round_bf16(kc), oracle.round_bf16(kr), 2, round_inputs=False)
+    torch.testing.assert_close(a, b, rtol=0, atol=0)
+
+
+def test_planted_heavy_hitters_are_recovered_on_tiny_case():
+    """Every planted key scores above 0.5 and is in the Top-K of X at rho = 0.3."""
+    c = synth.CASES["tiny"]
+    q, kc, kr = synth.make_proxy_qk(c)
+    X = oracle.score(q, kc, kr, c.chunk)
+    K = oracle.keep_count(c.N, 0.3)
+    assert K == 153
+    kept = oracle.topk(X.to(torch.float32).view(-1, c.N), K).view(c.L_s, c.H_kv, K)
+    plan = synth.plant_plan(c)
+    for l in range(c.L_s):
+        for h in range(c.H_kv):
+            pos = plan["pos"][l, h]
+            assert bool((X[l, h, pos] > 0.5).all())
+            assert set(pos.tolist()) <= set(kept[l, h].tolist())
+            assert int((X[l, h] > 0.5).sum()) == c.n_planted
+
+
+def test_keep_count_and_layer_pairing_and_windows():
+    assert oracle.keep_count(512, 0.3) == 153 and oracle.keep_count(8192, 0.3) == 2457
+    assert [oracle.keep_count(32768, r) for r in (0.1, 0.3, 0.5, 0.9)] == [3276, 9830, 16384, 29491]
+    assert oracle.keep_count(170000, 0.3) == 51000 and oracle.keep_count(3, 0.1) == 1 and oracle.keep_count(5, 1.0) == 5
+    with pytest.raises(ValueError):
+        oracle.keep_count(10, 0.0)
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "layer_pairing.txt")
+    n = 0
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        head, tail = line.split(":")
+        L_s, L_l = map(int, head.split())
+        assert [v + 1 for v in oracle.layer_pairing(L_s, L_l)] == list(map(int, tail.split()))
+        n += 1
+    assert n == 3
+    assert oracle.window_spans(2048) == [(0, 2048)] and oracle.window_spans(100) == [(0, 100)]
+    assert oracle.window_spans(2049) == [(0, 2048), (1024, 2049)]
+    assert oracle.window_spans(3072) == [(0, 2048), (1024, 3072)]
+    assert oracle.window_spans(5000) == [(0, 2048), (1024, 3072), (2048, 4096), (3072, 5000)]
+    for N in (2048, 2049, 3072, 5000, 32768, 170000):
+        cover = np.zeros(N, dtype=int)
+        spans = oracle.window_spans(N)
+        for s, e in spans:
+            assert s % 1024 == 0 and 0 < e - s <= 2048
+            cover[s:e] += 1
+        assert cover.min() >= 1 and cover.max() <= 2
+        assert (cover[:min(N, 1024)] == 1).all()
+    assert len(oracle.window_spans(32768)) == 31 and sum(e - s for s, e in oracle.window_spans(32768)) == 63488
+    assert len(oracle.window_spans(170000)) == 166 and sum(e - s for s, e in oracle.window_spans(170000)) == 338960
