@@ -1,0 +1,97 @@
+// Host-side state behind the opaque proxykv_ctx: configuration, device workspace and the device
+// copy of the mapper weights.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/proxykv.h"
+
+namespace pkv {
+
+struct DeviceBuffer {
+  void* ptr = nullptr;
+  size_t bytes = 0;
+};
+
+// Device pointers into one allocation that holds the prepared mapper weights.
+struct EncoderLayerWeights {
+  const uint16_t* in_w;   // bf16 [3*d_time, d_time]
+  const float* in_b;      // [3*d_time]
+  const uint16_t* out_w;  // bf16 [d_time, d_time]
+  const float* out_b;
+  const float *ln1_g, *ln1_b;
+  const uint16_t* ffn1_w;  // bf16 [d_ffn, d_time]
+  const float* ffn1_b;
+  const uint16_t* ffn2_w;  // bf16 [d_time, d_ffn]
+  const float* ffn2_b;
+  const float *ln2_g, *ln2_b;
+};
+
+struct MapperWeights {
+  const float* conv1_w;                  // fp32 [c_mid, H_kv*3]
+  const float *bn1_scale, *bn1_shift;    // batch norm and conv bias folded: y = conv * scale + shift
+  const uint16_t* conv2_w;               // bf16 [d_time, 3*c_mid], k index = tap * c_mid + channel
+  const float *bn2_scale, *bn2_shift;
+  std::vector<EncoderLayerWeights> enc;
+  const uint16_t* kv_w;                  // bf16 [2*H_kv*d_head_x, d_time]: key rows, then value rows
+  const float* kv_b;                     // [2*H_kv*d_head_x]
+  const float* queries;                  // [H_l, d_head_x]
+  const float* out_w;                    // [d_head_x]
+  float out_b;
+  const float* pe;                       // fp32 [win, d_time] sinusoidal table
+};
+
+// Mapper activations for ONE proxy layer (the network runs once per distinct proxy layer).
+struct MapperWorkspace {
+  DeviceBuffer h1;       // bf16 [(N+2), c_mid]  stem conv1 output with one zero row at each end
+  DeviceBuffer z_local;  // fp32 [N, d_time]
+  DeviceBuffer x;        // fp32 [T, d_time]     residual stream over all window rows
+  DeviceBuffer xb;       // bf16 [T, d_time]     bf16 copy feeding the GEMMs
+  DeviceBuffer qk;       // bf16 [T, 2*d_time]   q and k of the current layer
+  DeviceBuffer vt;       // bf16 [n_win, heads, 64, win]  v transposed per window and head
+  DeviceBuffer ao;       // bf16 [T, d_time]     attention output
+  DeviceBuffer tmp;      // fp32 [T, d_time]     pre-norm sums
+  DeviceBuffer hid;      // bf16 [T, d_ffn]
+  DeviceBuffer zg;       // bf16 [N, d_time]     overlap-averaged encoder output
+  DeviceBuffer kv3;      // fp32 [N, 2*H_kv*d_head_x]
+};
+
+}  // namespace pkv
+
+struct proxykv_ctx {
+  proxykv_config cfg;
+  int last_hip_error = 0;
+  bool weights_set = false;
+  pkv::DeviceBuffer weight_blob;
+  pkv::MapperWeights w;
+  std::vector<int32_t> pairing;  // [L_l] 0-based proxy layer per target layer
+  // workspace
+  pkv::DeviceBuffer q_bf16, kctx_bf16, krec_bf16;  // bf16 copies of fp32 inputs
+  pkv::DeviceBuffer neg_lse;                       // fp32 [L_s, H_q, N_q]
+  pkv::DeviceBuffer x_ws;                          // fp32 [L_s, H_kv, N]
+  pkv::DeviceBuffer yhat_ws;                       // fp32 [L_l, H_l, N]
+  pkv::MapperWorkspace m;
+};
+
+namespace pkv {
+
+// Number of windows and total window rows for context length N.
+inline void window_plan(int64_t N, int win, int stride, int64_t* n_win, int64_t* total_rows) {
+  if (N <= win) {
+    *n_win = 1;
+    *total_rows = N;
+    return;
+  }
+  const int64_t k = (N - win + stride - 1) / stride + 1;
+  *n_win = k;
+  *total_rows = (k - 1) * (int64_t)win + (N - (k - 1) * (int64_t)stride);
+}
+
+// Runs the mapper for every distinct proxy layer; implemented in mapper.hip.
+// Returns a hipError_t; the workspace must already be large enough.
+hipError_t mapper_forward(proxykv_ctx* ctx, const float* x, int64_t N, float* yhat, hipStream_t stream);
+
+}  // namespace pkv

@@ -1,0 +1,27 @@
+// Launchers of the HIP kernels; each enqueues on `stream` and returns the launch's hipError_t.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pkv {
+
+// fp32 -> bf16 (round to nearest even), n elements.
+hipError_t launch_f32_to_bf16(const float* in, uint16_t* out, int64_t n, hipStream_t stream);
+
+// Scoring, pass 1: neg_lse[l, h, i] = -log2(sum_k 2^(c * <q_i, k>)) / c with c = log2(e) / sqrt(d),
+// the sum running over the N context keys and the visible reconstruction keys of query i.
+hipError_t launch_score_lse(const uint16_t* q, const uint16_t* k_ctx, const uint16_t* k_rec, float* neg_lse,
+                            int L_s, int H_q, int H_kv, int d, int64_t N, int64_t N_q, int chunk,
+                            hipStream_t stream);
+// Scoring, pass 2: x[l, g, n] = 2^(c * max over (head of group g, query i) of (<q_i, k_n> + neg_lse[l, h, i])).
+hipError_t launch_score_colmax(const uint16_t* q, const uint16_t* k_ctx, const float* neg_lse, float* x,
+                               int L_s, int H_q, int H_kv, int d, int64_t N, int64_t N_q,
+                               hipStream_t stream);
+
+hipError_t launch_topk(const float* scores, int64_t rows, int64_t N, int64_t K, int32_t* idx_out,
+                       hipStream_t stream);
+
+hipError_t launch_compact(const void* k_in, const void* v_in, const int32_t* idx, int64_t rows, int64_t N,
+                          int64_t K, int64_t row_bytes, void* k_out, void* v_out, hipStream_t stream);
+
+}  // namespace pkv

@@ -1,0 +1,213 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Integer and byte results are bit-exact; floating-point results are within
+|gpu - ref| <= 2e-3 + 1e-2 * |ref| (bf16 inputs, fp32 accumulation)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_16360_amd import binding as pk
+from paper_2605_16360_amd import synth
+
+pytestmark = pytest.mark.gpu
+ATOL, RTOL = 2e-3, 1e-2
+
+
+def assert_close(gpu: torch.Tensor, ref: torch.Tensor, what: str):
+    g, r = gpu.detach().double().cpu(), ref.double()
+    assert g.shape == r.shape, (g.shape, r.shape)
+    assert bool(torch.isfinite(g).all()), f"{what}: non-finite values"
+    err = (g - r).abs()
+    bound = ATOL + RTOL * r.abs()
+    worst = int(torch.argmax(err - bound))
+    assert bool((err <= bound).all()), (f"{what}: max abs err {float(err.max()):.3e}, worst at flat {worst}: "
+                                        f"gpu {float(g.flatten()[worst])} ref {float(r.flatten()[worst])}")
+
+
+def _ctx(case, weights=None):
+    ctx = pk.proxykv_create(pk.config_for_case(case))
+    if weights is not None:
+        pk.proxykv_set_mapper_weights(ctx, weights)
+    return ctx
+
+
+# ----------------------------------------------------------------------------------------------
+# top-k and compaction: bit-exact
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("N,K", [(1, 1), (17, 5), (1000, 300), (1024, 1024), (1025, 1), (5000, 1500), (32771, 9830),
+                                 (70001, 21000)])
+def test_topk_bit_exact(N, K):
+    ctx = _ctx(synth.CASES["tiny"])
+    g = torch.Generator().manual_seed(N + K)
+    s = torch.randn(7, N, generator=g)
+    s[1] = torch.round(s[1] * 4) / 4             # heavy ties
+    s[2] = 0.5                                   # all equal
+    s[3] = torch.round(s[3])
+    if N > 8:
+        s[4, ::5] = float("nan")
+        s[5, 1], s[5, 2], s[5, 3], s[5, 4] = -0.0, 0.0, float("inf"), float("-inf")
+        s[5, 5:] = torch.where(s[5, 5:].abs() < 0.5, torch.zeros(()), s[5, 5:])
+        s[5, 7::2] *= -1.0                       # produces -0.0 next to +0.0
+    s[6] = s[6] * 1e-3 + 0.25                    # narrow range: many shared high radix digits
+    ref = oracle.topk(s, K)
+    got = pk.proxykv_topk(ctx, s.cuda(), K)
+    torch.cuda.synchronize()
+    assert torch.equal(got.cpu(), ref)
+
+
+def test_compact_bit_exact():
+    ctx = _ctx(synth.CASES["tiny"])
+    g = torch.Generator().manual_seed(3)
+    for (L, H, N, D, K) in [(2, 3, 700, 128, 211), (1, 2, 130, 64, 130), (1, 1, 9, 128, 1)]:
+        kv = torch.randn(2, L, H, N, D, generator=g).to(torch.bfloat16)
+        s = torch.randn(L * H, N, generator=g)
+        idx = oracle.topk(s, K).view(L, H, K)
+        k_out, v_out = pk.proxykv_compact(ctx, kv[0].cuda(), kv[1].cuda(), idx.cuda())
+        torch.cuda.synchronize()
+        assert torch.equal(k_out.cpu().view(torch.int16), oracle.compact(kv[0], idx).view(torch.int16))
+        assert torch.equal(v_out.cpu().view(torch.int16), oracle.compact(kv[1], idx).view(torch.int16))
+
+
+# ----------------------------------------------------------------------------------------------
+# scoring
+# ----------------------------------------------------------------------------------------------
+
+SCORE_CASES = {
+    # several key/query tiles, ragged tails, chunk boundaries that cut query blocks
+    "d64_ragged": dict(L_s=2, H_q=4, H_kv=2, d=64, N=1000, N_q=700, chunk=300, n_planted=6),
+    "d64_gqa7": dict(L_s=1, H_q=14, H_kv=2, d=64, N=1500, N_q=1500, chunk=512, n_planted=8),
+    "d128": dict(L_s=2, H_q=6, H_kv=2, d=128, N=900, N_q=640, chunk=256, n_planted=6),
+    "one_query": dict(L_s=1, H_q=1, H_kv=1, d=64, N=5, N_q=1, chunk=1, n_planted=0),
+    "small_chunks": dict(L_s=1, H_q=2, H_kv=1, d=64, N=300, N_q=300, chunk=17, n_planted=3),
+}
+
+
+def _score_case(name):
+    return synth.scaled_case(synth.CASES["llama_8k"], name=name, L_l=1, H_l=2, **SCORE_CASES[name])
+
+
+@pytest.mark.parametrize("name", list(SCORE_CASES))
+def test_score_matches_oracle(name):
+    case = _score_case(name)
+    q, kc, kr = synth.make_proxy_qk(case)
+    ref = oracle.score(q.double(), kc.double(), kr.double(), case.chunk)
+    ctx = _ctx(case)
+    x = pk.proxykv_score(ctx, q.cuda(), kc.cuda(), kr.cuda(), case.chunk)
+    torch.cuda.synchronize()
+    assert_close(x, ref, f"score[{name}]")
+    assert float(x.min()) >= 0.0 and float(x.max()) <= 1.0 + 1e-5
+
+
+def test_score_tiny_case_fp32_inputs_and_planted_keys():
+    case = synth.CASES["tiny"]
+    q, kc, kr = synth.make_proxy_qk(case)
+    assert q.dtype == torch.float32
+    ref = oracle.score(q, kc, kr, case.chunk)          # the oracle rounds the inputs to bf16 itself
+    ctx = _ctx(case)
+    x = pk.proxykv_score(ctx, q.cuda(), kc.cuda(), kr.cuda(), case.chunk)
+    torch.cuda.synchronize()
+    assert_close(x, ref, "score[tiny]")
+    plan = synth.plant_plan(case)
+    K = pk.proxykv_keep_count(case.N, 0.3)
+    kept = pk.proxykv_topk(ctx, x, K).cpu()
+    for l in range(case.L_s):
+        for h in range(case.H_kv):
+            assert set(plan["pos"][l, h].tolist()) <= set(kept[l, h].tolist())
+            assert bool((x[l, h].cpu()[plan["pos"][l, h]] > 0.5).all())
+
+
+def test_score_uniform_rows_closed_form():
+    """Zero queries: every row is uniform and the score is exactly 1/(N+1)."""
+    case = synth.scaled_case(_score_case("d64_ragged"), n_planted=0)
+    q, kc, kr = synth.make_proxy_qk(case)
+    ctx = _ctx(case)
+    x = pk.proxykv_score(ctx, torch.zeros_like(q).cuda(), kc.cuda(), kr.cuda(), case.chunk)
+    torch.cuda.synchronize()
+    torch.testing.assert_close(x.cpu(), torch.full_like(x.cpu(), 1.0 / (case.N + 1)), rtol=1e-5, atol=0)
+
+
+# ----------------------------------------------------------------------------------------------
+# mapper
+# ----------------------------------------------------------------------------------------------
+
+MAP_CASES = {
+    "one_window": dict(L_s=1, H_kv=2, H_q=4, L_l=1, H_l=4, N=512),
+    "two_windows_ragged": dict(L_s=2, H_kv=8, H_q=8, L_l=3, H_l=8, N=2500),
+    "three_windows_short_tail": dict(L_s=1, H_kv=2, H_q=2, L_l=2, H_l=4, N=3100),
+}
+
+
+@pytest.mark.parametrize("name", list(MAP_CASES))
+def test_mapper_matches_oracle(name):
+    case = synth.scaled_case(synth.CASES["llama_8k"], name=name, N_q=64, chunk=64, n_planted=0, **MAP_CASES[name])
+    w = synth.make_mapper_weights(case.H_kv, case.H_l)
+    g = torch.Generator().manual_seed(17)
+    # score-like input: mostly small positive values with a few near one
+    X = torch.rand(case.L_s, case.H_kv, case.N, generator=g) ** 8
+    X = X.to(torch.float32)
+    ref = oracle.mapper(X, w, case.L_l)
+    ctx = _ctx(case, w)
+    y = pk.proxykv_map(ctx, X.cuda())
+    torch.cuda.synchronize()
+    assert_close(y, ref, f"map[{name}]")
+    pairing = pk.proxykv_layer_pairing(ctx.cfg)
+    for a in range(case.L_l):
+        for b in range(a + 1, case.L_l):
+            if pairing[a] == pairing[b]:
+                assert torch.equal(y[a], y[b])
+
+
+# ----------------------------------------------------------------------------------------------
+# whole path
+# ----------------------------------------------------------------------------------------------
+
+def _band_check(y_ref: torch.Tensor, idx_gpu: torch.Tensor, K: int):
+    """Every token whose oracle score clears the K-th score by more than the tolerance is kept, every
+    token that misses it by more than the tolerance is dropped; exact equality when the K-th and
+    (K+1)-th oracle scores are further apart than the tolerance."""
+    rows, N = y_ref.shape
+    exact = 0
+    for r in range(rows):
+        srt = torch.sort(y_ref[r], descending=True).values
+        sK = float(srt[K - 1])
+        tau = 2.0 * (ATOL + RTOL * abs(sK))
+        kept = torch.zeros(N, dtype=torch.bool)
+        kept[idx_gpu[r].long()] = True
+        assert int(kept.sum()) == K and bool((idx_gpu[r][1:] > idx_gpu[r][:-1]).all())
+        assert bool(kept[y_ref[r] > sK + tau].all()), f"row {r}: a clearly-in token was dropped"
+        assert not bool(kept[y_ref[r] < sK - tau].any()), f"row {r}: a clearly-out token was kept"
+        if K < N and float(srt[K - 1] - srt[K]) > tau:
+            ref_idx = oracle.topk(y_ref[r:r + 1].float(), K)[0]
+            assert torch.equal(idx_gpu[r].cpu(), ref_idx)
+            exact += 1
+    return exact
+
+
+def test_prune_tiny_case_end_to_end():
+    case = synth.CASES["tiny"]
+    q, kc, kr = synth.make_proxy_qk(case)
+    k_t, v_t = synth.make_target_kv(case)
+    w = synth.make_mapper_weights(case.H_kv, case.H_l)
+    X_ref, Y_ref, idx_ref, K_ref, V_ref = oracle.prune(q, kc, kr, case.chunk, 0.3, w, k_t, v_t)
+    ctx = _ctx(case, w)
+    x = torch.empty(case.L_s, case.H_kv, case.N, dtype=torch.float32, device="cuda")
+    y = torch.empty(case.L_l, case.H_l, case.N, dtype=torch.float32, device="cuda")
+    k_out, v_out, idx, K = pk.proxykv_prune(ctx, q.cuda(), kc.cuda(), kr.cuda(), case.chunk, 0.3, k_t.cuda(), v_t.cuda(),
+                                            x_out=x, yhat_out=y)
+    torch.cuda.synchronize()
+    assert K == 153 == idx_ref.shape[-1]
+    assert_close(x, X_ref, "prune.x")
+    assert_close(y, Y_ref, "prune.yhat")
+    _band_check(Y_ref.view(-1, case.N), idx.cpu().view(-1, K), K)
+    # given the GPU's own scores, selection and compaction are exact
+    idx_same = oracle.topk(y.cpu().view(-1, case.N), K).view(case.L_l, case.H_l, K)
+    assert torch.equal(idx.cpu(), idx_same)
+    assert torch.equal(k_out.cpu().view(torch.int16), oracle.compact(k_t, idx_same).view(torch.int16))
+    assert torch.equal(v_out.cpu().view(torch.int16), oracle.compact(v_t, idx_same).view(torch.int16))
+    # a second call on the same context gives the same bits
+    k2, v2, idx2, _ = pk.proxykv_prune(ctx, q.cuda(), kc.cuda(), kr.cuda(), case.chunk, 0.3, k_t.cuda(), v_t.cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(idx2, idx) and torch.equal(k2.view(torch.int16), k_out.view(torch.int16))
