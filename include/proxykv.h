@@ -92,7 +92,7 @@ int proxykv_destroy(proxykv_ctx* ctx);
  *         queries [H_l, d_head_x], out.weight [d_head_x], out.bias [1]    (Sec. 4.1, Eq. 3) */
 size_t proxykv_mapper_weight_count(const proxykv_config* cfg);
 /* Copies the blob (HOST pointer, n_floats as above) to the device, pre-rounding matrix operands to
- * bf16 and folding the inference-mode batch-norm statistics into per-channel scale/shift.
+ * fp16 and folding the inference-mode batch-norm statistics into per-channel scale/shift.
  * Synchronous. */
 int proxykv_set_mapper_weights(proxykv_ctx* ctx, const float* blob_host, size_t n_floats);
 
@@ -128,7 +128,7 @@ int proxykv_score(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const 
  * positions restarting in every window, post-norm encoder layers (ReLU FFN) on windows
  * [stride*k, min(stride*k + win, N)), outputs averaged where windows overlap; stage 3: per-token
  * attention of the H_l learned queries over H_kv projected slots, then a linear map to one logit.
- * Matrix products take bf16 operands and accumulate in fp32; the rest is fp32.
+ * Matrix products take IEEE half (fp16) operands and accumulate in fp32; the rest is fp32.
  * Needs proxykv_set_mapper_weights (ESTATE otherwise). */
 int proxykv_map(proxykv_ctx* ctx, const float* x, int64_t N, float* yhat, void* stream);
 

@@ -19,11 +19,19 @@ unspecified hyper-parameters (stem width, encoder flavour, stage-3 sizes) has
 nothing in the paper to be pinned to: parity unpinned against the authors'
 mapper, pinned only to the definition written here.
 
-Precision: the paper runs its models in 16-bit precision (App. B).  The
-reading taken for the mapper is that every matrix-product operand (GEMM,
-second stem convolution, attention) is a bf16 value while sums, normalisation,
-softmax, GELU and the residual stream are kept wide.  `round_operands=False`
-switches the operand rounding off, which is what the library pins use.
+Precision: the paper runs its models in 16-bit precision (App. B) and says
+nothing about the mapper's own arithmetic.  The proxy's Q/K are bf16 values.
+The reading taken for the mapper is that every matrix-product operand (GEMM,
+second stem convolution, attention) is a 16-bit IEEE half (fp16) value while
+sums, normalisation, softmax, GELU and the residual stream are kept wide.
+Half rather than bf16 because activations are re-rounded some thirty times on
+the way through the encoder: two correct implementations whose wide values
+differ in the last bit round a few activations differently, and that
+difference grows to the size of the rounding step itself; with bf16's 8-bit
+significand this alone exceeds the tolerance asked of the mapped scores
+(2e-3 + 1e-2 |ref|), with half's 11 bits it stays an order of magnitude below.
+`round_operands=False` switches the operand rounding off, which is what the
+library pins use.
 """
 from __future__ import annotations
 
@@ -45,8 +53,15 @@ def round_bf16(x: torch.Tensor) -> torch.Tensor:
     return x.to(torch.float32).to(torch.bfloat16).to(F64)
 
 
-def _maybe_round(x: torch.Tensor, on: bool) -> torch.Tensor:
-    return round_bf16(x) if on else x.to(F64)
+def round_f16(x: torch.Tensor) -> torch.Tensor:
+    """Round to the nearest IEEE half value (ties to even), returned as float64."""
+    return x.to(torch.float32).to(torch.float16).to(F64)
+
+
+def _maybe_round(x: torch.Tensor, on: bool, fmt: str = "f16") -> torch.Tensor:
+    if not on:
+        return x.to(F64)
+    return round_bf16(x) if fmt == "bf16" else round_f16(x)
 
 
 def keep_count(N: int, keep_ratio: float) -> int:
@@ -166,9 +181,9 @@ def score(q_rec: torch.Tensor, k_ctx: torch.Tensor, k_rec: torch.Tensor, chunk: 
     X = torch.empty(L_s, H_kv, N, dtype=F64)
     for l in range(L_s):
         for h in range(H_kv):
-            X[l, h] = score_unit(_maybe_round(q_rec[l, h * G:(h + 1) * G], round_inputs),
-                                 _maybe_round(k_ctx[l, h], round_inputs),
-                                 _maybe_round(k_rec[l, h], round_inputs), chunk, reduce)
+            X[l, h] = score_unit(_maybe_round(q_rec[l, h * G:(h + 1) * G], round_inputs, "bf16"),
+                                 _maybe_round(k_ctx[l, h], round_inputs, "bf16"),
+                                 _maybe_round(k_rec[l, h], round_inputs, "bf16"), chunk, reduce)
     return X
 
 
@@ -208,7 +223,7 @@ def stem(U: torch.Tensor, w: Weights, round_operands: bool = True) -> torch.Tens
     BatchNorm in inference mode with stored statistics, eps 1e-5; GELU in its
     exact erf form; the convolution runs once over the whole sequence.  The
     first convolution works on the raw fp32 scores; the second one is a matrix
-    product and takes bf16 operands.
+    product and takes half-precision operands.
     """
     U = U.to(F64)
     a1 = _conv1d_k3(U, w["stem.conv1.weight"], w["stem.conv1.bias"])
@@ -315,7 +330,7 @@ def head_cross_attention(z_global: torch.Tensor, w: Weights, round_operands: boo
     score.  Returns the raw logit Y_hat [H_l, N] (the sigmoid of Sec. 4.2 is
     monotone, so the Top-K is the same).  Readings: D_head and H_s follow from
     the weight shapes; projections carry biases.  The two projections are matrix
-    products with bf16 operands; the per-token attention is wide."""
+    products with half-precision operands; the per-token attention is wide."""
     N, D = z_global.shape
     Ql = w["head.queries"].to(F64)
     H_l, dh = Ql.shape

@@ -130,12 +130,24 @@ int reserve_all(proxykv_ctx* ctx, int64_t N, int64_t N_q, bool score_part, bool 
   return rc;
 }
 
-uint16_t host_bf16(float f) {
-  uint32_t u;
-  memcpy(&u, &f, 4);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+// fp32 -> IEEE half bits, round to nearest even (subnormals and overflow to infinity included)
+uint16_t host_f16(float f) {
+  uint32_t x;
+  memcpy(&x, &f, 4);
+  const uint16_t sign = (uint16_t)((x >> 16) & 0x8000u);
+  const uint32_t ax = x & 0x7fffffffu;
+  if (ax > 0x7f800000u) return (uint16_t)(sign | 0x7e00u);
+  if (ax >= 0x477ff000u) return (uint16_t)(sign | 0x7c00u);  // >= 65520 rounds to infinity
+  if (ax < 0x38800000u) {                                      // below 2^-14: half subnormal, unit 2^-24
+    float a;
+    memcpy(&a, &ax, 4);
+    return (uint16_t)(sign | (uint32_t)nearbyint((double)a * 16777216.0));
+  }
+  const uint32_t mant = ax & 0x7fffffu, exp = (ax >> 23) - 127 + 15;
+  uint32_t h = (exp << 10) | (mant >> 13);
+  const uint32_t rem = mant & 0x1fffu;
+  if (rem > 0x1000u || (rem == 0x1000u && (h & 1u))) ++h;
+  return (uint16_t)(sign | h);
 }
 
 // Builds the prepared weight image on the host: a byte vector plus offsets of every section.
@@ -147,11 +159,11 @@ struct Stager {
     memcpy(bytes.data() + off, src, n * 4);
     return off;
   }
-  size_t put_bf16(const float* src, size_t n) {
+  size_t put_f16(const float* src, size_t n) {
     const size_t off = (bytes.size() + 255) & ~(size_t)255;
     bytes.resize(off + n * 2);
     uint16_t* d = reinterpret_cast<uint16_t*>(bytes.data() + off);
-    for (size_t i = 0; i < n; ++i) d[i] = host_bf16(src[i]);
+    for (size_t i = 0; i < n; ++i) d[i] = host_f16(src[i]);
     return off;
   }
 };
@@ -291,7 +303,7 @@ int proxykv_set_mapper_weights(proxykv_ctx* ctx, const float* blob, size_t n_flo
   for (size_t co = 0; co < D; ++co)
     for (size_t ci = 0; ci < C1; ++ci)
       for (size_t tap = 0; tap < 3; ++tap) c2r[(co * 3 + tap) * C1 + ci] = c2w[(co * C1 + ci) * 3 + tap];
-  const size_t o_c2w = st.put_bf16(c2r.data(), c2r.size());
+  const size_t o_c2w = st.put_f16(c2r.data(), c2r.size());
   size_t o_s2, o_h2;
   fold(c2b, g2, b2, m2, v2, D, &o_s2, &o_h2);
   struct EncOff {
@@ -300,15 +312,15 @@ int proxykv_set_mapper_weights(proxykv_ctx* ctx, const float* blob, size_t n_flo
   std::vector<EncOff> eo(c.n_enc_layers);
   for (int i = 0; i < c.n_enc_layers; ++i) {
     EncOff& e = eo[i];
-    e.in_w = st.put_bf16(take(3 * D * D), 3 * D * D);
+    e.in_w = st.put_f16(take(3 * D * D), 3 * D * D);
     e.in_b = st.put_f32(take(3 * D), 3 * D);
-    e.out_w = st.put_bf16(take(D * D), D * D);
+    e.out_w = st.put_f16(take(D * D), D * D);
     e.out_b = st.put_f32(take(D), D);
     e.ln1_g = st.put_f32(take(D), D);
     e.ln1_b = st.put_f32(take(D), D);
-    e.f1_w = st.put_bf16(take(F * D), F * D);
+    e.f1_w = st.put_f16(take(F * D), F * D);
     e.f1_b = st.put_f32(take(F), F);
-    e.f2_w = st.put_bf16(take(D * F), D * F);
+    e.f2_w = st.put_f16(take(D * F), D * F);
     e.f2_b = st.put_f32(take(D), D);
     e.ln2_g = st.put_f32(take(D), D);
     e.ln2_b = st.put_f32(take(D), D);
@@ -323,7 +335,7 @@ int proxykv_set_mapper_weights(proxykv_ctx* ctx, const float* blob, size_t n_flo
   memcpy(kvw.data() + Hs * dh * D, vw, Hs * dh * D * 4);
   memcpy(kvb.data(), kb, Hs * dh * 4);
   memcpy(kvb.data() + Hs * dh, vb, Hs * dh * 4);
-  const size_t o_kvw = st.put_bf16(kvw.data(), kvw.size());
+  const size_t o_kvw = st.put_f16(kvw.data(), kvw.size());
   const size_t o_kvb = st.put_f32(kvb.data(), kvb.size());
   const size_t o_q = st.put_f32(take(Hl * dh), Hl * dh);
   const size_t o_ow = st.put_f32(take(dh), dh);

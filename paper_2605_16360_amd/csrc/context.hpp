@@ -18,14 +18,14 @@ struct DeviceBuffer {
 
 // Device pointers into one allocation that holds the prepared mapper weights.
 struct EncoderLayerWeights {
-  const uint16_t* in_w;   // bf16 [3*d_time, d_time]
+  const uint16_t* in_w;   // fp16 [3*d_time, d_time]
   const float* in_b;      // [3*d_time]
-  const uint16_t* out_w;  // bf16 [d_time, d_time]
+  const uint16_t* out_w;  // fp16 [d_time, d_time]
   const float* out_b;
   const float *ln1_g, *ln1_b;
-  const uint16_t* ffn1_w;  // bf16 [d_ffn, d_time]
+  const uint16_t* ffn1_w;  // fp16 [d_ffn, d_time]
   const float* ffn1_b;
-  const uint16_t* ffn2_w;  // bf16 [d_time, d_ffn]
+  const uint16_t* ffn2_w;  // fp16 [d_time, d_ffn]
   const float* ffn2_b;
   const float *ln2_g, *ln2_b;
 };
@@ -33,10 +33,10 @@ struct EncoderLayerWeights {
 struct MapperWeights {
   const float* conv1_w;                  // fp32 [c_mid, H_kv*3]
   const float *bn1_scale, *bn1_shift;    // batch norm and conv bias folded: y = conv * scale + shift
-  const uint16_t* conv2_w;               // bf16 [d_time, 3*c_mid], k index = tap * c_mid + channel
+  const uint16_t* conv2_w;               // fp16 [d_time, 3*c_mid], k index = tap * c_mid + channel
   const float *bn2_scale, *bn2_shift;
   std::vector<EncoderLayerWeights> enc;
-  const uint16_t* kv_w;                  // bf16 [2*H_kv*d_head_x, d_time]: key rows, then value rows
+  const uint16_t* kv_w;                  // fp16 [2*H_kv*d_head_x, d_time]: key rows, then value rows
   const float* kv_b;                     // [2*H_kv*d_head_x]
   const float* queries;                  // [H_l, d_head_x]
   const float* out_w;                    // [d_head_x]
@@ -46,16 +46,16 @@ struct MapperWeights {
 
 // Mapper activations for ONE proxy layer (the network runs once per distinct proxy layer).
 struct MapperWorkspace {
-  DeviceBuffer h1;       // bf16 [(N+2), c_mid]  stem conv1 output with one zero row at each end
+  DeviceBuffer h1;       // fp16 [(N+2), c_mid]  stem conv1 output with one zero row at each end
   DeviceBuffer z_local;  // fp32 [N, d_time]
   DeviceBuffer x;        // fp32 [T, d_time]     residual stream over all window rows
-  DeviceBuffer xb;       // bf16 [T, d_time]     bf16 copy feeding the GEMMs
-  DeviceBuffer qk;       // bf16 [T, 2*d_time]   q and k of the current layer
-  DeviceBuffer vt;       // bf16 [n_win, heads, 64, win]  v transposed per window and head
-  DeviceBuffer ao;       // bf16 [T, d_time]     attention output
+  DeviceBuffer xb;       // fp16 [T, d_time]     fp16 copy feeding the GEMMs
+  DeviceBuffer qk;       // fp16 [T, 2*d_time]   q and k of the current layer
+  DeviceBuffer vt;       // fp16 [n_win, heads, 64, win]  v transposed per window and head
+  DeviceBuffer ao;       // fp16 [T, d_time]     attention output
   DeviceBuffer tmp;      // fp32 [T, d_time]     pre-norm sums
-  DeviceBuffer hid;      // bf16 [T, d_ffn]
-  DeviceBuffer zg;       // bf16 [N, d_time]     overlap-averaged encoder output
+  DeviceBuffer hid;      // fp16 [T, d_ffn]
+  DeviceBuffer zg;       // fp16 [N, d_time]     overlap-averaged encoder output
   DeviceBuffer kv3;      // fp32 [N, 2*H_kv*d_head_x]
 };
 

@@ -1,12 +1,12 @@
 // HybridAxialMapper forward (paper Sec. 4.1) for one proxy layer at a time:
-//   stage 1  conv stem            stem_conv1_kernel (fp32 ALU) + conv 2 as a bf16 MFMA GEMM whose A rows
+//   stage 1  conv stem            stem_conv1_kernel (fp32 ALU) + conv 2 as an fp16 MFMA GEMM whose A rows
 //                                 are overlapping 3-token spans of the padded conv-1 output
 //   stage 2  time-axis encoder    gather_pe_kernel, then per layer: QKV GEMM -> window attention ->
 //                                 out-proj GEMM (+residual) -> LayerNorm -> FFN GEMMs -> LayerNorm;
 //                                 all sliding windows of the layer are batched along the GEMM M axis
 //            overlap averaging    overlap_avg_kernel
 //   stage 3  head-axis attention  K/V projection GEMM + stage3_kernel (per token, fp32 ALU)
-// Matrix products take bf16 operands and accumulate in fp32 on v_mfma_f32_32x32x16_bf16; the
+// Matrix products take IEEE half (fp16) operands and accumulate in fp32 on v_mfma_f32_32x32x16_f16; the
 // residual stream, normalisation, softmax and GELU are fp32.
 #include "common.hpp"
 #include "context.hpp"
@@ -16,7 +16,7 @@ namespace pkv {
 namespace {
 
 typedef float f32x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kNegInf = -__builtin_huge_valf();
 constexpr int kDT = 512;    // d_time
@@ -26,13 +26,13 @@ constexpr int kHeads = 8;   // encoder heads, 64 wide
 
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 
-__device__ __forceinline__ uint16_t to_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+__device__ __forceinline__ uint16_t to_h(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
 
 // 8 chunks of 16 bytes per 128-byte LDS row, XOR-swizzled (see score.hip)
 __device__ __forceinline__ int swz8(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
 // ------------------------------------------------------------------------------------------
-// stage 1, first convolution: h1[t+1, c] = bf16(GELU(scale[c] * sum_{h,tap} w[c,h,tap] * x[h, t+tap-1] + shift[c]))
+// stage 1, first convolution: h1[t+1, c] = half(GELU(scale[c] * sum_{h,tap} w[c,h,tap] * x[h, t+tap-1] + shift[c]))
 // rows 0 and N+1 of h1 are zero (the padding of the second convolution).
 // grid ceil(N / 64), 256 threads; thread owns channels tid, tid+256, ...
 // ------------------------------------------------------------------------------------------
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void stem_conv1_kernel(const float* __restrict
           acc = __builtin_fmaf(wr[h * 3 + 2], xs[h][tt + 2], acc);
         }
       }
-      h1[(size_t)(t0 + tt + 1) * c_mid + c] = to_bf16(gelu_erf(__builtin_fmaf(acc, sc, sh)));
+      h1[(size_t)(t0 + tt + 1) * c_mid + c] = to_h(gelu_erf(__builtin_fmaf(acc, sc, sh)));
     }
     if (blockIdx.x == 0) h1[c] = 0;
     if (blockIdx.x == gridDim.x - 1) h1[(size_t)(N + 1) * c_mid + c] = 0;
@@ -74,16 +74,16 @@ __global__ __launch_bounds__(256) void stem_conv1_kernel(const float* __restrict
 }
 
 // ------------------------------------------------------------------------------------------
-// bf16 GEMM  C[M, Nn] = A[M, K] * W[Nn, K]^T  (+ epilogue), fp32 accumulation.
+// fp16 GEMM  C[M, Nn] = A[M, K] * W[Nn, K]^T  (+ epilogue), fp32 accumulation.
 // A rows start lda elements apart (lda < K gives the overlapping rows of the second convolution).
 // 128 x 128 block tile, K step 64, 4 waves in 2 x 2, each 64 x 64 = 2 x 2 MFMA tiles.
 // grid (Nn / 128, ceil(M / 128)); K % 64 == 0, Nn % 128 == 0.
 // ------------------------------------------------------------------------------------------
 enum Epilogue {
   kEpiAffineGeluF32,  // out_f32 = GELU(acc * p0[n] + p1[n])                       (second stem convolution)
-  kEpiQkv,            // acc + p0[n]: columns < 2*d_time -> out_bf16 [M, 2*d_time]; the rest -> vt (transposed)
+  kEpiQkv,            // acc + p0[n]: columns < 2*d_time -> out_h [M, 2*d_time]; the rest -> vt (transposed)
   kEpiBiasResidF32,   // out_f32 = acc + p0[n] + resid[m, n]
-  kEpiBiasReluBf16,   // out_bf16 = relu(acc + p0[n])
+  kEpiBiasReluH,   // out_h = relu(acc + p0[n])
   kEpiBiasF32         // out_f32 = acc + p0[n]
 };
 
@@ -92,12 +92,12 @@ struct EpiArgs {
   const float* p1;
   const float* resid;
   float* out_f32;
-  uint16_t* out_bf16;
+  uint16_t* out_h;
   uint16_t* vt;
 };
 
 template <int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __restrict__ A, int lda,
+__global__ __launch_bounds__(256, 2) void gemm_f16_kernel(const uint16_t* __restrict__ A, int lda,
                                                             const uint16_t* __restrict__ W, int M, int Nn, int K,
                                                             EpiArgs ep) {
   __shared__ u32x4 lds_a[128 * 8];
@@ -138,17 +138,17 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __res
     if (k0 + 64 < K) fetch(k0 + 64);
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 fa[2], fb[2];
+      f16x8 fa[2], fb[2];
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int ra_row = wm * 64 + i * 32 + l32, rb_row = wn * 64 + i * 32 + l32;
-        fa[i] = as_bf16x8(lds_a[ra_row * 8 + ((kk * 2 + half) ^ swz8(ra_row))]);
-        fb[i] = as_bf16x8(lds_b[rb_row * 8 + ((kk * 2 + half) ^ swz8(rb_row))]);
+        fa[i] = as_f16x8(lds_a[ra_row * 8 + ((kk * 2 + half) ^ swz8(ra_row))]);
+        fb[i] = as_f16x8(lds_b[rb_row * 8 + ((kk * 2 + half) ^ swz8(rb_row))]);
       }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = mfma_32x32x16(fa[i], fb[j], acc[i][j]);
+        for (int j = 0; j < 2; ++j) acc[i][j] = mfma_f16_32x32x16(fa[i], fb[j], acc[i][j]);
     }
   }
 
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __res
           if (n < 2 * kDT) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-              if (mb + e < M) ep.out_bf16[(size_t)(mb + e) * (2 * kDT) + n] = to_bf16(v[e] + p0);
+              if (mb + e < M) ep.out_h[(size_t)(mb + e) * (2 * kDT) + n] = to_h(v[e] + p0);
           } else {
             // v transposed: vt[window][head][dd][pos], pos = 16-token groups with bits 2 and 3 of the
             // in-group offset swapped, which is the order the P*V MFMA consumes keys in
@@ -181,14 +181,14 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __res
             const int pos = (p & ~15) | (w16 & 3) | ((w16 & 4) << 1) | ((w16 & 8) >> 1);
             uint16_t* dst = ep.vt + ((size_t)(wk * kHeads + hd) * 64 + dd) * kWin + pos;
             if (mb + 3 < M) {
-              bf16x4 pk;
+              f16x4 pk;
 #pragma unroll
-              for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(v[e] + p0);
-              *reinterpret_cast<bf16x4*>(dst) = pk;
+              for (int e = 0; e < 4; ++e) pk[e] = (_Float16)(v[e] + p0);
+              *reinterpret_cast<f16x4*>(dst) = pk;
             } else {
 #pragma unroll
               for (int e = 0; e < 4; ++e)
-                if (mb + e < M) dst[e] = to_bf16(v[e] + p0);
+                if (mb + e < M) dst[e] = to_h(v[e] + p0);
             }
           }
         } else {
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const uint16_t* __res
             const size_t o = (size_t)m * Nn + n;
             if constexpr (EPI == kEpiAffineGeluF32) ep.out_f32[o] = gelu_erf(__builtin_fmaf(v[e], p0, p1));
             else if constexpr (EPI == kEpiBiasResidF32) ep.out_f32[o] = v[e] + p0 + ep.resid[o];
-            else if constexpr (EPI == kEpiBiasReluBf16) ep.out_bf16[o] = to_bf16(__builtin_fmaxf(v[e] + p0, 0.0f));
+            else if constexpr (EPI == kEpiBiasReluH) ep.out_h[o] = to_h(__builtin_fmaxf(v[e] + p0, 0.0f));
             else ep.out_f32[o] = v[e] + p0;
           }
         }
@@ -223,11 +223,11 @@ __global__ __launch_bounds__(256) void gather_pe_kernel(const float* __restrict_
   const f32x4 b = *reinterpret_cast<const f32x4*>(pe + (size_t)p * kDT + c4 * 4);
   const f32x4 s = a + b;
   *reinterpret_cast<f32x4*>(x + (size_t)r * kDT + c4 * 4) = s;
-  *reinterpret_cast<bf16x4*>(xb + (size_t)r * kDT + c4 * 4) = __builtin_convertvector(s, bf16x4);
+  *reinterpret_cast<f16x4*>(xb + (size_t)r * kDT + c4 * 4) = __builtin_convertvector(s, f16x4);
 }
 
 // ------------------------------------------------------------------------------------------
-// LayerNorm over rows of 512 (eps 1e-5): x = LN(in) * g + b, plus a bf16 copy.  One wave per row.
+// LayerNorm over rows of 512 (eps 1e-5): x = LN(in) * g + b, plus an fp16 copy.  One wave per row.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict__ in, const float* __restrict__ g,
                                                          const float* __restrict__ b, float* __restrict__ x,
@@ -254,8 +254,8 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict_
   const f32x4 y0 = v0 * rstd * g0 + b0, y1 = v1 * rstd * g1 + b1;
   *reinterpret_cast<f32x4*>(x + (size_t)row * kDT + lane * 4) = y0;
   *reinterpret_cast<f32x4*>(x + (size_t)row * kDT + 256 + lane * 4) = y1;
-  *reinterpret_cast<bf16x4*>(xb + (size_t)row * kDT + lane * 4) = __builtin_convertvector(y0, bf16x4);
-  *reinterpret_cast<bf16x4*>(xb + (size_t)row * kDT + 256 + lane * 4) = __builtin_convertvector(y1, bf16x4);
+  *reinterpret_cast<f16x4*>(xb + (size_t)row * kDT + lane * 4) = __builtin_convertvector(y0, f16x4);
+  *reinterpret_cast<f16x4*>(xb + (size_t)row * kDT + 256 + lane * 4) = __builtin_convertvector(y1, f16x4);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
   if (i0 >= len) return;
   constexpr float c = 1.4426950408889634f * 0.125f;  // log2(e) / sqrt(64)
 
-  bf16x8 bq[2][4];
+  f16x8 bq[2][4];
   int qi[2];
 #pragma unroll
   for (int cs = 0; cs < 2; ++cs) {
@@ -285,7 +285,7 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
     const int row = qi[cs] < len ? qi[cs] : len - 1;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
-      bq[cs][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(qk + (size_t)(base + row) * (2 * kDT) + hd * 64 + kk * 16 + half * 8));
+      bq[cs][kk] = as_f16x8(*reinterpret_cast<const u32x4*>(qk + (size_t)(base + row) * (2 * kDT) + hd * 64 + kk * 16 + half * 8));
   }
   f32x16 o[2][2];  // [d half][query sub-tile]
 #pragma unroll
@@ -331,8 +331,8 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
           const int row = ks * 32 + l32;
-          const bf16x8 fk = as_bf16x8(lds_k[row * 8 + ((kk * 2 + half) ^ swz8(row))]);
-          s[ks] = mfma_32x32x16(fk, bq[cs][kk], s[ks]);
+          const f16x8 fk = as_f16x8(lds_k[row * 8 + ((kk * 2 + half) ^ swz8(row))]);
+          s[ks] = mfma_f16_32x32x16(fk, bq[cs][kk], s[ks]);
         }
         if (ragged) {
 #pragma unroll
@@ -370,13 +370,13 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
             p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[ks][u2 * 8 + e], c, nref));
             lsum += p[e];
           }
-          const bf16x8 pb = __builtin_convertvector(p, bf16x8);
+          const f16x8 pb = __builtin_convertvector(p, f16x8);
           const int u = ks * 2 + u2;
 #pragma unroll
           for (int ds = 0; ds < 2; ++ds) {
             const int row = ds * 32 + l32;  // V^T fragment: d row, 16-key step u
-            const bf16x8 fv = as_bf16x8(lds_v[row * 8 + ((u * 2 + half) ^ swz8(row))]);
-            o[ds][cs] = mfma_32x32x16(fv, pb, o[ds][cs]);
+            const f16x8 fv = as_f16x8(lds_v[row * 8 + ((u * 2 + half) ^ swz8(row))]);
+            o[ds][cs] = mfma_f16_32x32x16(fv, pb, o[ds][cs]);
           }
         }
       }
@@ -392,17 +392,17 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
       for (int ds = 0; ds < 2; ++ds)
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
-          bf16x4 pk;
+          f16x4 pk;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(o[ds][cs][rg * 4 + e] * inv);
-          *reinterpret_cast<bf16x4*>(dst + ds * 32 + rg * 8 + half * 4) = pk;
+          for (int e = 0; e < 4; ++e) pk[e] = (_Float16)(o[ds][cs][rg * 4 + e] * inv);
+          *reinterpret_cast<f16x4*>(dst + ds * 32 + rg * 8 + half * 4) = pk;
         }
     }
   }
 }
 
 // ------------------------------------------------------------------------------------------
-// overlap averaging: zg[t] = bf16(mean over the windows covering token t of x[row of t in that window])
+// overlap averaging: zg[t] = half(mean over the windows covering token t of x[row of t in that window])
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void overlap_avg_kernel(const float* __restrict__ x, uint16_t* __restrict__ zg,
                                                            int64_t N, int n_win) {
@@ -423,7 +423,7 @@ __global__ __launch_bounds__(256) void overlap_avg_kernel(const float* __restric
     cnt += 1.0f;
   }
   const f32x4 mean = sum / cnt;
-  *reinterpret_cast<bf16x4*>(zg + (size_t)t * kDT + c4 * 4) = __builtin_convertvector(mean, bf16x4);
+  *reinterpret_cast<f16x4*>(zg + (size_t)t * kDT + c4 * 4) = __builtin_convertvector(mean, f16x4);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -496,7 +496,7 @@ template <int EPI>
 hipError_t launch_gemm(const uint16_t* A, int lda, const uint16_t* W, int64_t M, int Nn, int K, const EpiArgs& ep,
                        hipStream_t stream) {
   dim3 grid((unsigned)(Nn / 128), (unsigned)((M + 127) / 128));
-  gemm_bf16_kernel<EPI><<<grid, 256, 0, stream>>>(A, lda, W, (int)M, Nn, K, ep);
+  gemm_f16_kernel<EPI><<<grid, 256, 0, stream>>>(A, lda, W, (int)M, Nn, K, ep);
   return hipGetLastError();
 }
 
@@ -556,7 +556,7 @@ hipError_t mapper_forward(proxykv_ctx* ctx, const float* x_in, int64_t N, float*
       layernorm_kernel<<<(unsigned)((T + 3) / 4), 256, 0, stream>>>(tmp, e.ln1_g, e.ln1_b, x, xb, T);
       PKV_TRY(hipGetLastError());
       EpiArgs e1 = {e.ffn1_b, nullptr, nullptr, nullptr, hid, nullptr};
-      PKV_TRY(launch_gemm<kEpiBiasReluBf16>(xb, kDT, e.ffn1_w, T, c.d_ffn, kDT, e1, stream));
+      PKV_TRY(launch_gemm<kEpiBiasReluH>(xb, kDT, e.ffn1_w, T, c.d_ffn, kDT, e1, stream));
       EpiArgs ef = {e.ffn2_b, nullptr, x, tmp, nullptr, nullptr};
       PKV_TRY(launch_gemm<kEpiBiasResidF32>(hid, c.d_ffn, e.ffn2_w, T, kDT, c.d_ffn, ef, stream));
       layernorm_kernel<<<(unsigned)((T + 3) / 4), 256, 0, stream>>>(tmp, e.ln2_g, e.ln2_b, x, xb, T);
