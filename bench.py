@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the ProxyKV hot path on one MI355X: one step = one proxykv_prune
+(score -> map -> top-k -> compact over all layers) on seeded synthetic inputs that are already
+resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--case llama_32k] [--keep-ratio 0.3]
+"""
+import argparse
+import json
+import sys
+import time
+
+
+def flops_score(case):
+    """Algorithmic QK^T flops of the two scoring passes (2*d per visited query-key pair; the causal
+    part of a reconstruction chunk is counted at its unmasked area)."""
+    full, rem = divmod(case.N_q, case.chunk)
+    tri = full * case.chunk * (case.chunk + 1) // 2 + rem * (rem + 1) // 2
+    per_pair = 2 * case.d * case.H_q * case.L_s
+    return per_pair * (case.N_q * case.N + tri), per_pair * case.N_q * case.N
+
+
+def bytes_topk_compact(case, K):
+    rows = case.L_l * case.H_l
+    topk = rows * (4 * case.N + 4 * K)
+    compact = 2 * rows * K * case.D * 2 * 2 + rows * K * 4
+    return topk, compact
+
+
+def cpu_baseline(case, keep_ratio, x_layer0):
+    """Times the CPU oracle on a bounded sample of the same workload and scales each stage linearly
+    to the full problem.  x_layer0: [H_kv, N] fp32 CPU tensor (one proxy layer's scores) used as the
+    mapper sample's input."""
+    import torch
+    import oracle
+    from paper_2605_16360_amd import synth
+
+    G = case.G
+    nq_s = min(case.N_q, case.chunk)                     # first reconstruction chunk of one (layer, KV head)
+    q = synth.normal_tensor((G, nq_s, case.d), 7, 11).to(torch.bfloat16).double()
+    kc = synth.normal_tensor((case.N, case.d), 7, 12).to(torch.bfloat16).double()
+    kr = synth.normal_tensor((nq_s, case.d), 7, 13).to(torch.bfloat16).double()
+    t0 = time.perf_counter()
+    oracle.score_unit(q, kc, kr, case.chunk)
+    t_score = (time.perf_counter() - t0) * (case.N_q / nq_s) * case.L_s * case.H_kv
+
+    n_map = min(case.N, 3072)                            # two overlapping encoder windows
+    w = synth.make_mapper_weights(case.H_kv, case.H_l)
+    t0 = time.perf_counter()
+    y = oracle.mapper_layer(x_layer0[:, :n_map].double(), w)
+    rows_s = sum(e - s for s, e in oracle.window_spans(n_map))
+    rows_f = sum(e - s for s, e in oracle.window_spans(case.N))
+    t_map = (time.perf_counter() - t0) * (rows_f / rows_s) * case.L_l
+
+    K = oracle.keep_count(case.N, keep_ratio)
+    rows_sel = min(8, case.L_l * case.H_l)
+    scores = synth.normal_tensor((rows_sel, case.N), 7, 14)
+    kv = synth.normal_tensor((rows_sel, case.N, case.D), 7, 15).to(torch.bfloat16)
+    t0 = time.perf_counter()
+    idx = oracle.topk(scores, K)
+    t_topk = (time.perf_counter() - t0) * (case.L_l * case.H_l / rows_sel)
+    t0 = time.perf_counter()
+    oracle.compact(kv, idx)
+    oracle.compact(kv, idx)
+    t_comp = (time.perf_counter() - t0) * (case.L_l * case.H_l / rows_sel)
+    total = t_score + t_map + t_topk + t_comp
+    del y
+    return {
+        "value": case.N / total, "unit": "scored context tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+        "sample": (f"score: first chunk ({nq_s} queries x {G} heads) of one (layer, KV head) of {case.L_s * case.H_kv}; "
+                   f"mapper: one forward on the first {n_map} tokens ({rows_s} of {rows_f} window rows) of {case.L_l} "
+                   f"forwards; top-k and compaction: {rows_sel} of {case.L_l * case.H_l} rows; each stage scaled "
+                   f"linearly to the full problem (extrapolated)"),
+        "extrapolated_seconds": {"score": t_score, "map": t_map, "topk": t_topk, "compact": t_comp},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--case", default="llama_32k")
+    ap.add_argument("--keep-ratio", type=float, default=0.3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_16360_amd import binding as pk
+    from paper_2605_16360_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    case = synth.CASES[args.case]
+    dev = torch.device("cuda:0")
+    q, kc, kr = synth.make_proxy_qk(case, device=dev)
+    k_t, v_t = synth.make_target_kv(case, device=dev)
+    w = synth.make_mapper_weights(case.H_kv, case.H_l)
+    ctx = pk.proxykv_create(pk.config_for_case(case))
+    pk.proxykv_set_mapper_weights(ctx, w)
+    pk.proxykv_reserve(ctx, case.N, case.N_q)
+    K = pk.proxykv_keep_count(case.N, args.keep_ratio)
+    k_out = torch.empty(case.L_l, case.H_l, K, case.D, dtype=torch.bfloat16, device=dev)
+    v_out = torch.empty_like(k_out)
+    idx = torch.empty(case.L_l, case.H_l, K, dtype=torch.int32, device=dev)
+    x = torch.empty(case.L_s, case.H_kv, case.N, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        pk.proxykv_prune(ctx, q, kc, kr, case.chunk, args.keep_ratio, k_t, v_t, k_out, v_out, idx, x_out=x, stream=stream)
+
+    pk.proxykv_profile_enable(ctx, True)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    stage_ms = {s: 0.0 for s in pk.STAGES}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+        for s, v in pk.proxykv_profile_read(ctx).items():   # HIP events recorded on the work stream
+            stage_ms[s] += v / args.steps
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+
+    f_lse, f_col = flops_score(case)
+    kern = {"score_lse": f_lse, "score_colmax": f_col}
+    dominant = max(kern, key=lambda s: stage_ms[s])
+    peak_tflops = 2500.0
+    achieved = kern[dominant] / (stage_ms[dominant] * 1e-3) / 1e12
+    b_topk, b_comp = bytes_topk_compact(case, K)
+    hbm_gbps = (b_topk + b_comp) / ((stage_ms["topk"] + stage_ms["compact"]) * 1e-3) / 1e9
+    out = {
+        "metric": "scored context tokens/s (score+map+TopK+compact)",
+        "value": case.N / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": case.name, "N": case.N, "N_q": case.N_q, "chunk": case.chunk, "keep_ratio": args.keep_ratio,
+                   "K": K, "proxy": [case.L_s, case.H_q, case.H_kv, case.d], "target": [case.L_l, case.H_l, case.D]},
+        "roofline": {"bound": "mfma", "kernel": dominant, "achieved": achieved, "peak": peak_tflops, "unit": "TFLOP/s",
+                     "frac": achieved / peak_tflops, "traffic": None},
+        "stages_ms": stage_ms,
+        "score_mfma_frac": (f_lse + f_col) / ((stage_ms["score_lse"] + stage_ms["score_colmax"]) * 1e-3) / 1e12 / peak_tflops,
+        "topk_compact_hbm": {"bytes": b_topk + b_comp, "achieved": hbm_gbps, "peak": 8000.0, "unit": "GB/s",
+                             "frac": hbm_gbps / 8000.0},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(case, args.keep_ratio, x[0].float().cpu())
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

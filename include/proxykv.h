@@ -157,6 +157,16 @@ int proxykv_prune(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const 
                   const void* k_in, const void* v_in, void* k_out, void* v_out, int32_t* idx_out,
                   float* x_out, float* yhat_out, int64_t* K_host, void* stream);
 
+/* Stage timing of proxykv_prune, for benchmarks.  With timing switched on, proxykv_prune records a
+ * HIP event on its stream at each stage boundary (no synchronisation, no allocation in the call).
+ * proxykv_profile_read waits for the last event of the most recent proxykv_prune and writes the
+ * PROXYKV_N_STAGES durations in milliseconds to ms_host (HOST array): score pass 1 (row
+ * log-sum-exp), score pass 2 (column max), mapper, top-k, compaction.  ESTATE if timing is off or
+ * no complete proxykv_prune has been recorded since it was switched on. */
+#define PROXYKV_N_STAGES 5
+int proxykv_profile_enable(proxykv_ctx* ctx, int on);
+int proxykv_profile_read(proxykv_ctx* ctx, float* ms_host);
+
 /* Static description of a status code. */
 const char* proxykv_strerror(int status);
 /* hipError_t of the last failed HIP call on this context (0 if none). */

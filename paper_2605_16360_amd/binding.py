@@ -21,8 +21,9 @@ EXPORTS = [
     "proxykv_default_mapper", "proxykv_create", "proxykv_destroy", "proxykv_mapper_weight_count",
     "proxykv_set_mapper_weights", "proxykv_workspace_bytes", "proxykv_reserve", "proxykv_keep_count",
     "proxykv_layer_pairing", "proxykv_score", "proxykv_map", "proxykv_topk", "proxykv_compact", "proxykv_prune",
-    "proxykv_strerror", "proxykv_last_hip_error",
+    "proxykv_profile_enable", "proxykv_profile_read", "proxykv_strerror", "proxykv_last_hip_error",
 ]
+STAGES = ("score_lse", "score_colmax", "map", "topk", "compact")
 
 
 class proxykv_config(ctypes.Structure):
@@ -69,6 +70,8 @@ def load() -> ctypes.CDLL:
     lib.proxykv_compact.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp, vp]
     lib.proxykv_prune.argtypes = [vp, vp, vp, vp, i32, i64, i64, i32, f64, vp, vp, vp, vp, vp, vp, vp,
                                   ctypes.POINTER(i64), vp]
+    lib.proxykv_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.proxykv_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.proxykv_strerror.argtypes = [ctypes.c_int]; lib.proxykv_strerror.restype = ctypes.c_char_p
     lib.proxykv_last_hip_error.argtypes = [vp]
     _lib = lib
@@ -182,6 +185,17 @@ def proxykv_layer_pairing(cfg: proxykv_config):
     arr = (ctypes.c_int32 * cfg.L_l)()
     _check(load().proxykv_layer_pairing(ctypes.byref(cfg), arr), "proxykv_layer_pairing")
     return list(arr)
+
+
+def proxykv_profile_enable(ctx: Context, on: bool) -> None:
+    _check(load().proxykv_profile_enable(ctx.handle, int(bool(on))), "proxykv_profile_enable", ctx.handle)
+
+
+def proxykv_profile_read(ctx: Context) -> Dict[str, float]:
+    """Stage durations (ms) of the most recent proxykv_prune; waits for it to finish."""
+    ms = (ctypes.c_float * len(STAGES))()
+    _check(load().proxykv_profile_read(ctx.handle, ms), "proxykv_profile_read", ctx.handle)
+    return dict(zip(STAGES, (float(v) for v in ms)))
 
 
 def _dev_ptr(t: Optional[torch.Tensor], name: str, dtype=None) -> Optional[int]:

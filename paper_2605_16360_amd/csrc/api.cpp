@@ -174,6 +174,14 @@ void free_buffer(DeviceBuffer& b) {
   b.bytes = 0;
 }
 
+// Records stage boundary `i` on the stream when stage timing is switched on.
+int mark(proxykv_ctx* ctx, int i, hipStream_t stream) {
+  if (!ctx->profile) return PROXYKV_OK;
+  PKV_HIP(ctx, hipEventRecord(ctx->ev[i], stream));
+  ctx->ev_recorded[i] = true;
+  return PROXYKV_OK;
+}
+
 int score_impl(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const void* k_rec, int32_t dtype, int64_t N,
                int64_t N_q, int32_t chunk, float* x_out, hipStream_t stream) {
   const proxykv_config& c = ctx->cfg;
@@ -194,8 +202,12 @@ int score_impl(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const voi
   }
   if ((rc = reserve_all(ctx, N, N_q, true, false, false, stream))) return rc;
   float* nl = (float*)ctx->neg_lse.ptr;
+  int rcm;
+  if ((rcm = mark(ctx, 0, stream))) return rcm;
   PKV_HIP(ctx, pkv::launch_score_lse(q, kc, kr, nl, c.L_s, c.H_q, c.H_kv, c.d, N, N_q, chunk, stream));
+  if ((rcm = mark(ctx, 1, stream))) return rcm;
   PKV_HIP(ctx, pkv::launch_score_colmax(q, kc, nl, x_out, c.L_s, c.H_q, c.H_kv, c.d, N, N_q, stream));
+  if ((rcm = mark(ctx, 2, stream))) return rcm;
   return PROXYKV_OK;
 }
 
@@ -245,12 +257,14 @@ int proxykv_destroy(proxykv_ctx* ctx) {
                          &ctx->x_ws,        &ctx->yhat_ws, &ctx->m.h1,     &ctx->m.z_local, &ctx->m.x,
                          &ctx->m.xb,        &ctx->m.qk,    &ctx->m.vt,     &ctx->m.ao,      &ctx->m.tmp,
                          &ctx->m.hid,       &ctx->m.zg,    &ctx->m.kv3};
-  bool any = false;
+  bool any = ctx->ev_created;
   for (DeviceBuffer* b : all) any = any || b->ptr;
   if (any) {
     (void)hipSetDevice(ctx->cfg.device);
     (void)hipDeviceSynchronize();
     for (DeviceBuffer* b : all) free_buffer(*b);
+    if (ctx->ev_created)
+      for (int i = 0; i < PROXYKV_N_STAGES + 1; ++i) (void)hipEventDestroy(ctx->ev[i]);
   }
   delete ctx;
   return PROXYKV_OK;
@@ -471,9 +485,34 @@ int proxykv_prune(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const 
   float* y = yhat_out ? yhat_out : (float*)ctx->yhat_ws.ptr;
   if ((rc = score_impl(ctx, q_rec, k_ctx, k_rec, dtype, N, N_q, chunk, x, s))) return rc;
   if ((rc = map_impl(ctx, x, N, y, s))) return rc;
+  if ((rc = mark(ctx, 3, s))) return rc;
   PKV_HIP(ctx, pkv::launch_topk(y, rows, N, K, idx_out, s));
+  if ((rc = mark(ctx, 4, s))) return rc;
   PKV_HIP(ctx, pkv::launch_compact(k_in, v_in, idx_out, rows, N, K, (int64_t)c.D * 2, k_out, v_out, s));
+  if ((rc = mark(ctx, 5, s))) return rc;
   if (K_host) *K_host = K;
+  return PROXYKV_OK;
+}
+
+int proxykv_profile_enable(proxykv_ctx* ctx, int on) {
+  if (!ctx) return PROXYKV_EINVAL;
+  if (on && !ctx->ev_created) {
+    PKV_HIP(ctx, hipSetDevice(ctx->cfg.device));
+    for (int i = 0; i < PROXYKV_N_STAGES + 1; ++i) PKV_HIP(ctx, hipEventCreate(&ctx->ev[i]));
+    ctx->ev_created = true;
+  }
+  ctx->profile = on != 0;
+  for (int i = 0; i < PROXYKV_N_STAGES + 1; ++i) ctx->ev_recorded[i] = false;
+  return PROXYKV_OK;
+}
+
+int proxykv_profile_read(proxykv_ctx* ctx, float* ms_host) {
+  if (!ctx || !ms_host) return PROXYKV_EINVAL;
+  if (!ctx->profile || !ctx->ev_created) return PROXYKV_ESTATE;
+  for (int i = 0; i < PROXYKV_N_STAGES + 1; ++i)
+    if (!ctx->ev_recorded[i]) return PROXYKV_ESTATE;
+  PKV_HIP(ctx, hipEventSynchronize(ctx->ev[PROXYKV_N_STAGES]));
+  for (int i = 0; i < PROXYKV_N_STAGES; ++i) PKV_HIP(ctx, hipEventElapsedTime(&ms_host[i], ctx->ev[i], ctx->ev[i + 1]));
   return PROXYKV_OK;
 }
 

@@ -65,6 +65,10 @@ struct proxykv_ctx {
   proxykv_config cfg;
   int last_hip_error = 0;
   bool weights_set = false;
+  // stage timing: events at the boundaries of the PROXYKV_N_STAGES stages of proxykv_prune
+  bool profile = false, ev_created = false;
+  hipEvent_t ev[PROXYKV_N_STAGES + 1] = {};
+  bool ev_recorded[PROXYKV_N_STAGES + 1] = {};
   pkv::DeviceBuffer weight_blob;
   pkv::MapperWeights w;
   std::vector<int32_t> pairing;  // [L_l] 0-based proxy layer per target layer
