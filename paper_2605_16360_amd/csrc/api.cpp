@@ -38,7 +38,7 @@ int validate_config(const proxykv_config* c) {
   if ((c->D * 2) % 16 != 0) return PROXYKV_EUNSUPPORTED;
   if (c->reduce != PROXYKV_REDUCE_MAX) return PROXYKV_EUNSUPPORTED;
   if (c->d_time != 512 || c->n_enc_heads != 8 || c->d_head_x != 64 || c->win != 2048 || c->stride != 1024 ||
-      c->c_mid % 128 != 0 || c->d_ffn % 128 != 0 || c->H_kv > 16 || c->H_l > 64)
+      c->c_mid % 256 != 0 || c->d_ffn % 256 != 0 || c->H_kv > 16 || c->H_l > 64)
     return PROXYKV_EUNSUPPORTED;
   return PROXYKV_OK;
 }
@@ -86,21 +86,22 @@ Sizes workspace_sizes(const proxykv_config& c, int64_t N, int64_t N_q) {
   Sizes s;
   int64_t n_win, T;
   pkv::window_plan(N, c.win, c.stride, &n_win, &T);
-  const size_t Tp = (size_t)T, Np = (size_t)N, dt = (size_t)c.d_time;
+  // rows of GEMM outputs (and of the residuals they read) are padded to the GEMM's 256-row tile
+  const size_t Tp = ((size_t)T + 255) / 256 * 256, Np = (size_t)N, Npad = (Np + 255) / 256 * 256, dt = (size_t)c.d_time;
   s.neg_lse = (size_t)c.L_s * c.H_q * (size_t)N_q * 4;
   s.x_ws = (size_t)c.L_s * c.H_kv * Np * 4;
   s.yhat_ws = (size_t)c.L_l * c.H_l * Np * 4;
   s.h1 = (Np + 2) * (size_t)c.c_mid * 2;
-  s.z_local = Np * dt * 4;
+  s.z_local = Npad * dt * 4;
   s.x = Tp * dt * 4;
   s.xb = Tp * dt * 2;
-  s.qk = Tp * 2 * dt * 2;
+  s.qk = Tp * 3 * dt * 2;
   s.vt = (size_t)n_win * dt * (size_t)c.win * 2;
   s.ao = Tp * dt * 2;
   s.tmp = Tp * dt * 4;
   s.hid = Tp * (size_t)c.d_ffn * 2;
   s.zg = Np * dt * 2;
-  s.kv3 = Np * 2 * (size_t)c.H_kv * (size_t)c.d_head_x * 4;
+  s.kv3 = Npad * (size_t)pkv::kv3_stride(c) * 4;
   return s;
 }
 
@@ -344,7 +345,9 @@ int proxykv_set_mapper_weights(proxykv_ctx* ctx, const float* blob, size_t n_flo
   const float* kb = take(Hs * dh);
   const float* vw = take(Hs * dh * D);
   const float* vb = take(Hs * dh);
-  std::vector<float> kvw(2 * Hs * dh * D), kvb(2 * Hs * dh);
+  // rows padded with zeros to the GEMM's 256-column tile (pkv::kv3_stride)
+  const size_t kv_rows = (size_t)pkv::kv3_stride(c);
+  std::vector<float> kvw(kv_rows * D, 0.0f), kvb(kv_rows, 0.0f);
   memcpy(kvw.data(), kw, Hs * dh * D * 4);
   memcpy(kvw.data() + Hs * dh * D, vw, Hs * dh * D * 4);
   memcpy(kvb.data(), kb, Hs * dh * 4);

@@ -45,18 +45,21 @@ struct MapperWeights {
 };
 
 // Mapper activations for ONE proxy layer (the network runs once per distinct proxy layer).
+// Row length of the stage-3 K/V projection's output: 2*H_kv*d_head_x rounded up to the GEMM's column tile.
+inline int kv3_stride(const proxykv_config& c) { return (2 * c.H_kv * c.d_head_x + 255) / 256 * 256; }
+
 struct MapperWorkspace {
   DeviceBuffer h1;       // fp16 [(N+2), c_mid]  stem conv1 output with one zero row at each end
   DeviceBuffer z_local;  // fp32 [N, d_time]
   DeviceBuffer x;        // fp32 [T, d_time]     residual stream over all window rows
   DeviceBuffer xb;       // fp16 [T, d_time]     fp16 copy feeding the GEMMs
-  DeviceBuffer qk;       // fp16 [T, 2*d_time]   q and k of the current layer
+  DeviceBuffer qk;       // fp16 [T, 3*d_time]   q, k and v of the current layer
   DeviceBuffer vt;       // fp16 [n_win, heads, 64, win]  v transposed per window and head
   DeviceBuffer ao;       // fp16 [T, d_time]     attention output
   DeviceBuffer tmp;      // fp32 [T, d_time]     pre-norm sums
   DeviceBuffer hid;      // fp16 [T, d_ffn]
   DeviceBuffer zg;       // fp16 [N, d_time]     overlap-averaged encoder output
-  DeviceBuffer kv3;      // fp32 [N, 2*H_kv*d_head_x]
+  DeviceBuffer kv3;      // fp32 [N, kv3_stride]  stage-3 keys then values of every slot, then padding
 };
 
 }  // namespace pkv

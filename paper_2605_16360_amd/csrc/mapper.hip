@@ -76,135 +76,267 @@ __global__ __launch_bounds__(256) void stem_conv1_kernel(const float* __restrict
 // ------------------------------------------------------------------------------------------
 // fp16 GEMM  C[M, Nn] = A[M, K] * W[Nn, K]^T  (+ epilogue), fp32 accumulation.
 // A rows start lda elements apart (lda < K gives the overlapping rows of the second convolution).
-// 128 x 128 block tile, K step 64, 4 waves in 2 x 2, each 64 x 64 = 2 x 2 MFMA tiles.
-// grid (Nn / 128, ceil(M / 128)); K % 64 == 0, Nn % 128 == 0.
+//
+// Persistent kernel, one 512-thread workgroup per CU.  Block tile 256 (rows of A) x 256 (rows of W),
+// K step 64 (full 128-byte lines per row), 8 waves in 4 x 2, each 64 x 128 = 2 x 4 MFMA tiles.  A tile
+// of this shape needs 1 byte from L2 per 128 flop; smaller tiles are bound by the L2 -> CU path, not by
+// the matrix pipe.
+//
+// The A rows go on the MFMA M axis and the W rows on the N axis, so a lane owns output COLUMNS.  The
+// W rows of a wave's 128-column block are staged in the order n = 4*l + jn (l = lane & 31, jn = MFMA
+// tile), so a lane holds four adjacent columns in its four tiles and every store instruction writes
+// whole 256-byte (fp16) or 512-byte (fp32) row segments, 8 or 16 bytes per lane.  Output (and residual)
+// buffers have their row count padded to a multiple of 256, so the epilogue has no row predicate; rows
+// at and past M are written with values that nobody reads.
+//
+// The K steps of all tiles of a workgroup form one stream: two LDS stages of 64 KB and ONE barrier
+// per step.  A step is four phases of 8 MFMAs; the fragments of phase kk+1 are read from LDS between
+// the MFMAs of phase kk (phase 3 reads phase 0 of the next step, behind the barrier), step s+1 goes
+// from registers to LDS during phase 2 and step s+2 is fetched from global memory into registers
+// during phase 3 -- across tile boundaries, so the next tile's loads are in flight during an epilogue.
+// The issue order is written out and pinned with scheduling barriers.
+//
+// Tile order: blocks are dealt round-robin to the 8 XCDs by the hardware, so XCD x = block % 8 takes the
+// row tiles x, x+8, ... and its workgroups take that list's (row tile, column tile) pairs round-robin:
+// the Nn / 256 column tiles of one row tile run at the same time on one XCD and share its L2 copy of
+// the A rows.
+// K % 64 == 0, Nn % 256 == 0.
 // ------------------------------------------------------------------------------------------
 enum Epilogue {
   kEpiAffineGeluF32,  // out_f32 = GELU(acc * p0[n] + p1[n])                       (second stem convolution)
-  kEpiQkv,            // acc + p0[n]: columns < 2*d_time -> out_h [M, 2*d_time]; the rest -> vt (transposed)
-  kEpiBiasResidF32,   // out_f32 = acc + p0[n] + resid[m, n]
-  kEpiBiasReluH,   // out_h = relu(acc + p0[n])
+  kEpiBiasH,          // out_h = acc + p0[n]
+  kEpiBiasReluH,      // out_h = relu(acc + p0[n])
   kEpiBiasF32         // out_f32 = acc + p0[n]
 };
 
 struct EpiArgs {
   const float* p0;
   const float* p1;
-  const float* resid;
   float* out_f32;
   uint16_t* out_h;
-  uint16_t* vt;
 };
 
+#ifdef PKV_PLAIN_STORE
+#define PKV_ST(ptr, val) (*(ptr) = (val))
+#else
+#define PKV_ST(ptr, val) __builtin_nontemporal_store((val), (ptr))
+#endif
+
+constexpr int kGemmBM = 256, kGemmBN = 256, kGemmBK = 64;
+constexpr int kGemmStageU4 = (kGemmBM + kGemmBN) * (kGemmBK / 8);  // 16-byte units per stage
+constexpr int kXcds = 8;
+
 template <int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_f16_kernel(const uint16_t* __restrict__ A, int lda,
+__global__ __launch_bounds__(512, 1) void gemm_f16_kernel(const uint16_t* __restrict__ A, int lda,
                                                             const uint16_t* __restrict__ W, int M, int Nn, int K,
                                                             EpiArgs ep) {
-  __shared__ u32x4 lds_a[128 * 8];
-  __shared__ u32x4 lds_b[128 * 8];
+  extern __shared__ u32x4 lds[];  // 2 stages
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
   const int wm = wave >> 1, wn = wave & 1;
-  const int n0 = blockIdx.x * 128, m0 = blockIdx.y * 128;
+  const int n_tiles = Nn / kGemmBN;
+  const int nk = K / kGemmBK;
+  const int xcd = blockIdx.x % kXcds, wg = blockIdx.x / kXcds, wg_per_xcd = gridDim.x / kXcds;
+  // tile `it` of this workgroup: entry it * wg_per_xcd + wg of the XCD's list
+  auto tile_of = [&](int it, int& m0, int& n0) {
+    const int u = it * wg_per_xcd + wg;
+    m0 = ((u / n_tiles) * kXcds + xcd) * kGemmBM;
+    n0 = (u % n_tiles) * kGemmBN;
+    return m0 < M;
+  };
+  int my_tiles = 0;
+  {
+    int a, b;
+    while (tile_of(my_tiles, a, b)) ++my_tiles;
+  }
+  const int total = my_tiles * nk;
+  if (total == 0) return;
+#ifdef PKV_STAGGER
+  for (int i = 0; i < (wg & 7) * PKV_STAGGER; ++i) __builtin_amdgcn_s_sleep(127);
+#endif
 
-  f32x16 acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-  u32x4 ra[4], rb[4];
-  auto fetch = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + 256 * i, row = id >> 3, ch = id & 7;
-      int m = m0 + row;
+  // staging: thread t moves chunk t % 8 of LDS rows t / 8 + 64 * i (i < 4: A rows, i >= 4: W rows).
+  // LDS row wl = 64 (i - 4) + t / 8 of the W part holds W row n0 + 128 (wl / 128) + 4 (wl % 32) + (wl % 128) / 32.
+  const int srow = tid >> 3, sch = tid & 7;
+  const int sslot = srow * 8 + (sch ^ swz8(srow));  // swz8(srow + 64 * i) == swz8(srow)
+  u32x4 rg[8];
+  int f_m0 = 0, f_n0 = 0, f_k = 0, f_it = 0;  // position of the next step to fetch
+  tile_of(0, f_m0, f_n0);
+  auto fetch_one = [&](int i) {
+    const int k0 = f_k * kGemmBK + sch * 8;
+    if (i < 4) {
+      int m = f_m0 + srow + 64 * i;
       m = m < M ? m : M - 1;
-      ra[i] = *reinterpret_cast<const u32x4*>(A + (size_t)m * lda + k0 + ch * 8);
-      rb[i] = *reinterpret_cast<const u32x4*>(W + (size_t)(n0 + row) * K + k0 + ch * 8);
+      rg[i] = *reinterpret_cast<const u32x4*>(A + (size_t)m * lda + k0);
+    } else {
+      const int wl = srow + 64 * (i - 4);
+      const int n = f_n0 + (wl & 128) + 4 * (wl & 31) + ((wl & 127) >> 5);
+      rg[i] = *reinterpret_cast<const u32x4*>(W + (size_t)n * K + k0);
     }
   };
-  fetch(0);
-  for (int k0 = 0; k0 < K; k0 += 64) {
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + 256 * i, row = id >> 3, ch = id & 7;
-      lds_a[row * 8 + (ch ^ swz8(row))] = ra[i];
-      lds_b[row * 8 + (ch ^ swz8(row))] = rb[i];
-    }
-    __syncthreads();
-    if (k0 + 64 < K) fetch(k0 + 64);
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      f16x8 fa[2], fb[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int ra_row = wm * 64 + i * 32 + l32, rb_row = wn * 64 + i * 32 + l32;
-        fa[i] = as_f16x8(lds_a[ra_row * 8 + ((kk * 2 + half) ^ swz8(ra_row))]);
-        fb[i] = as_f16x8(lds_b[rb_row * 8 + ((kk * 2 + half) ^ swz8(rb_row))]);
+  // moves on to the following step; past the end it stays on the last step (re-reads valid memory)
+  auto fetch_advance = [&]() {
+    if (++f_k == nk) {
+      if (f_it + 1 < my_tiles) {
+        f_k = 0;
+        ++f_it;
+        tile_of(f_it, f_m0, f_n0);
+      } else {
+        f_k = nk - 1;
       }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = mfma_f16_32x32x16(fa[i], fb[j], acc[i][j]);
     }
-  }
+  };
 
-  // epilogue: lane holds column n, rows m_base + (r/4)*8 + half*4 + r%4
+  f32x16 acc[2][4];
+  auto zero_acc = [&]() {
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int n = n0 + wn * 64 + j * 32 + l32;
-    const float p0 = ep.p0[n];
-    const float p1 = (EPI == kEpiAffineGeluF32) ? ep.p1[n] : 0.0f;
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int jn = 0; jn < 4; ++jn) acc[i][jn] = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  };
+  zero_acc();
+  // bias (and scale) of the current tile's columns n .. n+3, loaded when the tile starts: a load inside
+  // the epilogue would have to wait for the prefetch of the next step as well
+  f32x4 p0, p1 = {0.0f, 0.0f, 0.0f, 0.0f};
+  auto load_bias = [&](int it) {
+    int m0, n0;
+    tile_of(it < my_tiles ? it : my_tiles - 1, m0, n0);
+    const int n = n0 + wn * 128 + 4 * l32;
+    p0 = *reinterpret_cast<const f32x4*>(ep.p0 + n);
+    if constexpr (EPI == kEpiAffineGeluF32) p1 = *reinterpret_cast<const f32x4*>(ep.p1 + n);
+  };
+  load_bias(0);
+
+  // prologue: step 0 to LDS, step 1 in registers, fragments of (step 0, phase 0) in registers
+#pragma unroll
+  for (int i = 0; i < 8; ++i) fetch_one(i);
+  fetch_advance();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) lds[sslot + 64 * 8 * i] = rg[i];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) fetch_one(i);
+  fetch_advance();
+  __syncthreads();
+  const int fsw = swz8(l32);  // all fragment rows of this lane are l32 plus a multiple of 32
+  const int xrow = (wm * 64 + l32) * 8, wrow = (kGemmBM + wn * 128 + l32) * 8;
+  f16x8 fx[2][2], fw[2][4];
+  auto read_frag = [&](const u32x4* st, int kk, int set, int which) {
+    const int slot = (kk * 2 + half) ^ fsw;
+    if (which < 2) fx[set][which] = as_f16x8(st[xrow + which * 32 * 8 + slot]);
+    else fw[set][which - 2] = as_f16x8(st[wrow + (which - 2) * 32 * 8 + slot]);
+  };
+#pragma unroll
+  for (int wh = 0; wh < 6; ++wh) read_frag(lds, 0, 0, wh);
+
+  for (int s = 0; s < total; ++s) {
+    const u32x4* st = lds + (s & 1) * kGemmStageU4;
+    u32x4* st_next = lds + ((s + 1) & 1) * kGemmStageU4;
+    static_for<4>([&](auto kc) {
+      constexpr int kk = decltype(kc)::value, cur = kk & 1, nxt = cur ^ 1;
+      if constexpr (kk == 3) {
+        // every wave has read the last fragments of this step and written its part of step s+1
+        __syncthreads();
+      }
+      static_for<8>([&](auto jc) {
+        constexpr int j = decltype(jc)::value, i = j >> 2, jn = j & 3;
+        acc[i][jn] = mfma_f16_32x32x16(fx[cur][i], fw[cur][jn], acc[i][jn]);
+        if constexpr (j < 6) {
+          if constexpr (kk < 3) read_frag(st, kk + 1, nxt, j);
+          else read_frag(st_next, 0, nxt, j);
+        }
+        if constexpr (kk == 2) st_next[sslot + 64 * 8 * j] = rg[j];
+        if constexpr (kk == 3) fetch_one(j);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    });
+    fetch_advance();
+    if (s % nk != nk - 1) continue;
+#ifdef PKV_NO_EPI
+    if (acc[0][0][0] != 12345.678f) { zero_acc(); continue; }
+#endif
+
+    // epilogue: lane holds columns n .. n+3; register r of tile (i, jn) holds row mb + (r/4)*8 + r%4
+    int m0, n0;
+    tile_of(s / nk, m0, n0);
+    const int n = n0 + wn * 128 + 4 * l32;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
+      const size_t ob = (size_t)(m0 + wm * 64 + i * 32 + half * 4) * Nn + n;
 #pragma unroll
-      for (int rg = 0; rg < 4; ++rg) {
-        const int mb = m0 + wm * 64 + i * 32 + rg * 8 + half * 4;  // 4 consecutive rows mb .. mb+3
-        if (mb >= M) continue;
-        float v[4];
+      for (int qd = 0; qd < 4; ++qd) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][rg * 4 + e];
-        if constexpr (EPI == kEpiQkv) {
-          if (n < 2 * kDT) {
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const int r = qd * 4 + e4;
+          f32x4 v = {acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]};
+          const size_t o = ob + (size_t)(qd * 8 + e4) * Nn;
+#ifdef PKV_EPI_NOSTORE
+          if (p0[0] != 12345.678f) continue;
+#endif
+          if constexpr (EPI == kEpiAffineGeluF32) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (mb + e < M) ep.out_h[(size_t)(mb + e) * (2 * kDT) + n] = to_h(v[e] + p0);
+            for (int e = 0; e < 4; ++e) v[e] = gelu_erf(__builtin_fmaf(v[e], p0[e], p1[e]));
+            PKV_ST(reinterpret_cast<f32x4*>(ep.out_f32 + o), v);
+          } else if constexpr (EPI == kEpiBiasH) {
+            PKV_ST(reinterpret_cast<f16x4*>(ep.out_h + o), __builtin_convertvector(v + p0, f16x4));
+          } else if constexpr (EPI == kEpiBiasReluH) {
+            v += p0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaxf(v[e], 0.0f);
+            PKV_ST(reinterpret_cast<f16x4*>(ep.out_h + o), __builtin_convertvector(v, f16x4));
           } else {
-            // v transposed: vt[window][head][dd][pos], pos = 16-token groups with bits 2 and 3 of the
-            // in-group offset swapped, which is the order the P*V MFMA consumes keys in
-            const int f = n - 2 * kDT, hd = f >> 6, dd = f & 63;
-            const int wk = mb / kWin, p = mb % kWin;
-            const int w16 = p & 15;
-            const int pos = (p & ~15) | (w16 & 3) | ((w16 & 4) << 1) | ((w16 & 8) >> 1);
-            uint16_t* dst = ep.vt + ((size_t)(wk * kHeads + hd) * 64 + dd) * kWin + pos;
-            if (mb + 3 < M) {
-              f16x4 pk;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) pk[e] = (_Float16)(v[e] + p0);
-              *reinterpret_cast<f16x4*>(dst) = pk;
-            } else {
-#pragma unroll
-              for (int e = 0; e < 4; ++e)
-                if (mb + e < M) dst[e] = to_h(v[e] + p0);
-            }
-          }
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int m = mb + e;
-            if (m >= M) continue;
-            const size_t o = (size_t)m * Nn + n;
-            if constexpr (EPI == kEpiAffineGeluF32) ep.out_f32[o] = gelu_erf(__builtin_fmaf(v[e], p0, p1));
-            else if constexpr (EPI == kEpiBiasResidF32) ep.out_f32[o] = v[e] + p0 + ep.resid[o];
-            else if constexpr (EPI == kEpiBiasReluH) ep.out_h[o] = to_h(__builtin_fmaxf(v[e] + p0, 0.0f));
-            else ep.out_f32[o] = v[e] + p0;
+            PKV_ST(reinterpret_cast<f32x4*>(ep.out_f32 + o), v + p0);
           }
         }
       }
     }
+    zero_acc();
+    load_bias(s / nk + 1);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// vt[window][head][dd][pos] = v of window row (window, p), taken from columns [2*d_time, 3*d_time) of the
+// QKV GEMM's output; pos = p with bits 2 and 3 of its offset inside a 16-token group swapped, which is
+// the order the P*V MFMA of the attention kernel consumes keys in.  A 64-token block with at least one row
+// below T is written whole (rows at and past T repeat row T-1: finite values under a zero probability).
+// grid (win / 64, heads, n_win), 256 threads: a 64 token x 64 dd tile goes through LDS.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void v_transpose_kernel(const uint16_t* __restrict__ qkv, uint16_t* __restrict__ vt,
+                                                           int64_t T) {
+  __shared__ uint16_t tile[64][64 + 2];
+  const int hd = blockIdx.y, wk = blockIdx.z, p0 = blockIdx.x * 64, tid = threadIdx.x;
+  const int64_t base = (int64_t)wk * kWin + p0;
+  if (base >= T) return;  // the attention kernel reads whole 64-token blocks up to the window's last token
+  {  // 64 rows x 8 chunks of 16 bytes = 512 chunks, two per thread
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int id = tid + 256 * i, row = id >> 3, ch = id & 7;
+      int64_t r = base + row;
+      r = r < T ? r : T - 1;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(qkv + (size_t)r * (3 * kDT) + 2 * kDT + hd * 64 + ch * 8);
+      uint32_t* d = reinterpret_cast<uint32_t*>(&tile[row][ch * 8]);
+      d[0] = v[0];
+      d[1] = v[1];
+      d[2] = v[2];
+      d[3] = v[3];
+    }
+  }
+  __syncthreads();
+  // thread writes 16 bytes = 8 consecutive positions of one dd row: positions q0 .. q0+7 of a 16-group are
+  // tokens with bits 2 and 3 swapped
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int id = tid + 256 * i, dd = id >> 3, q0 = (id & 7) * 8;
+    uint16_t o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int pos = q0 + e, w16 = pos & 15;
+      const int tok = (pos & ~15) | (w16 & 3) | ((w16 & 4) << 1) | ((w16 & 8) >> 1);
+      o[e] = tile[tok][dd];
+    }
+    u32x4 pk;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) pk[e] = (uint32_t)o[2 * e] | ((uint32_t)o[2 * e + 1] << 16);
+    *reinterpret_cast<u32x4*>(vt + ((size_t)(wk * kHeads + hd) * 64 + dd) * kWin + p0 + q0) = pk;
   }
 }
 
@@ -227,7 +359,9 @@ __global__ __launch_bounds__(256) void gather_pe_kernel(const float* __restrict_
 }
 
 // ------------------------------------------------------------------------------------------
-// LayerNorm over rows of 512 (eps 1e-5): x = LN(in) * g + b, plus an fp16 copy.  One wave per row.
+// Post-norm residual step over rows of 512 (eps 1e-5): x = LN(x + in) * g + b, plus an fp16 copy.  One
+// wave per row.  The residual is added here and not in the producing GEMM's epilogue, where the loads
+// would stall the matrix pipe.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict__ in, const float* __restrict__ g,
                                                          const float* __restrict__ b, float* __restrict__ x,
@@ -236,8 +370,10 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict_
   if (row >= T) return;
   const int lane = threadIdx.x & 63;
   const float* src = in + (size_t)row * kDT;
-  f32x4 v0 = *reinterpret_cast<const f32x4*>(src + lane * 4);
-  f32x4 v1 = *reinterpret_cast<const f32x4*>(src + 256 + lane * 4);
+  f32x4 v0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + lane * 4));
+  f32x4 v1 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + 256 + lane * 4));
+  v0 += *reinterpret_cast<const f32x4*>(x + (size_t)row * kDT + lane * 4);
+  v1 += *reinterpret_cast<const f32x4*>(x + (size_t)row * kDT + 256 + lane * 4);
   float s = (v0[0] + v0[1]) + (v0[2] + v0[3]) + (v1[0] + v1[1]) + (v1[2] + v1[3]);
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
@@ -285,7 +421,7 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
     const int row = qi[cs] < len ? qi[cs] : len - 1;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
-      bq[cs][kk] = as_f16x8(*reinterpret_cast<const u32x4*>(qk + (size_t)(base + row) * (2 * kDT) + hd * 64 + kk * 16 + half * 8));
+      bq[cs][kk] = as_f16x8(*reinterpret_cast<const u32x4*>(qk + (size_t)(base + row) * (3 * kDT) + hd * 64 + kk * 16 + half * 8));
   }
   f32x16 o[2][2];  // [d half][query sub-tile]
 #pragma unroll
@@ -296,7 +432,7 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
       for (int r = 0; r < 16; ++r) o[ds][cs][r] = 0.0f;
   float m_run[2] = {-1.0e30f, -1.0e30f}, l_run[2] = {0.0f, 0.0f};
 
-  const uint16_t* kbase = qk + (size_t)base * (2 * kDT) + kDT + hd * 64;
+  const uint16_t* kbase = qk + (size_t)base * (3 * kDT) + kDT + hd * 64;
   const uint16_t* vbase = vt + (size_t)(wk * kHeads + hd) * 64 * kWin;
   u32x4 rk[2], rv[2];
   auto fetch = [&](int j0) {
@@ -305,7 +441,7 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
       const int id = tid + 256 * i, row = id >> 3, ch = id & 7;
       int j = j0 + row;
       j = j < len ? j : len - 1;
-      rk[i] = *reinterpret_cast<const u32x4*>(kbase + (size_t)j * (2 * kDT) + ch * 8);
+      rk[i] = *reinterpret_cast<const u32x4*>(kbase + (size_t)j * (3 * kDT) + ch * 8);
       rv[i] = *reinterpret_cast<const u32x4*>(vbase + (size_t)row * kWin + j0 + ch * 8);
     }
   };
@@ -433,11 +569,10 @@ __global__ __launch_bounds__(256) void overlap_avg_kernel(const float* __restric
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void stage3_kernel(const float* __restrict__ kv3, const float* __restrict__ queries,
                                                       const float* __restrict__ w_o, float b_o, float* __restrict__ yhat,
-                                                      int64_t N, int H_s, int H_l, int ll_lo, int ll_hi) {
+                                                      int64_t N, int H_s, int H_l, int row_f, int ll_lo, int ll_hi) {
   __shared__ float u_lds[256 * kMaxHs / 1];  // [token][slot], at most 256 tokens... sized for H_l = 1
   const int tok_per_block = 256 / H_l;
   const int64_t t0 = (int64_t)blockIdx.x * tok_per_block;
-  const int row_f = 2 * H_s * 64;
   // phase 1: u[token][s] = <w_o, V[s]>
   for (int i = threadIdx.x; i < tok_per_block * H_s; i += 256) {
     const int tt = i % tok_per_block, s = i / tok_per_block;
@@ -492,11 +627,26 @@ __global__ __launch_bounds__(256) void stage3_kernel(const float* __restrict__ k
   for (int ll = ll_lo; ll < ll_hi; ++ll) yhat[((size_t)ll * H_l + h) * N + t] = y;
 }
 
+constexpr int kGemmLdsBytes = 2 * kGemmStageU4 * 16;
+
 template <int EPI>
 hipError_t launch_gemm(const uint16_t* A, int lda, const uint16_t* W, int64_t M, int Nn, int K, const EpiArgs& ep,
-                       hipStream_t stream) {
-  dim3 grid((unsigned)(Nn / 128), (unsigned)((M + 127) / 128));
-  gemm_f16_kernel<EPI><<<grid, 256, 0, stream>>>(A, lda, W, (int)M, Nn, K, ep);
+                       int n_cu, hipStream_t stream) {
+  static bool attr_set = false;  // per instantiation; setting it again is harmless
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f16_kernel<EPI>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  if (Nn % kGemmBN != 0 || K % kGemmBK != 0 || M <= 0) return hipErrorInvalidValue;
+  const int m_tiles = (int)((M + kGemmBM - 1) / kGemmBM), n_tiles = Nn / kGemmBN;
+  // one workgroup per CU, a multiple of the XCD count, no more than there are tiles per XCD list
+  const int per_xcd_tiles = ((m_tiles + kXcds - 1) / kXcds) * n_tiles;
+  int wg_per_xcd = n_cu / kXcds;
+  if (wg_per_xcd < 1) wg_per_xcd = 1;
+  if (wg_per_xcd > per_xcd_tiles) wg_per_xcd = per_xcd_tiles;
+  gemm_f16_kernel<EPI><<<kXcds * wg_per_xcd, 512, kGemmLdsBytes, stream>>>(A, lda, W, (int)M, Nn, K, ep);
   return hipGetLastError();
 }
 
@@ -512,6 +662,9 @@ hipError_t mapper_forward(proxykv_ctx* ctx, const float* x_in, int64_t N, float*
   const proxykv_config& c = ctx->cfg;
   const MapperWeights& w = ctx->w;
   MapperWorkspace& m = ctx->m;
+  int n_cu = 0, dev = 0;
+  PKV_TRY(hipGetDevice(&dev));
+  PKV_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
   int64_t n_win, T;
   window_plan(N, c.win, c.stride, &n_win, &T);
   uint16_t* h1 = (uint16_t*)m.h1.ptr;
@@ -539,26 +692,28 @@ hipError_t mapper_forward(proxykv_ctx* ctx, const float* x_in, int64_t N, float*
     stem_conv1_kernel<<<(unsigned)((N + kStemTok - 1) / kStemTok), 256, 0, stream>>>(xl, w.conv1_w, w.bn1_scale, w.bn1_shift,
                                                                                     h1, c.H_kv, (int)N, c.c_mid);
     PKV_TRY(hipGetLastError());
-    EpiArgs e2 = {w.bn2_scale, w.bn2_shift, nullptr, z_local, nullptr, nullptr};
-    PKV_TRY(launch_gemm<kEpiAffineGeluF32>(h1, c.c_mid, w.conv2_w, N, kDT, 3 * c.c_mid, e2, stream));
+    EpiArgs e2 = {w.bn2_scale, w.bn2_shift, z_local, nullptr};
+    PKV_TRY(launch_gemm<kEpiAffineGeluF32>(h1, c.c_mid, w.conv2_w, N, kDT, 3 * c.c_mid, e2, n_cu, stream));
 
     // stage 2
     gather_pe_kernel<<<ew_blocks_T, 256, 0, stream>>>(z_local, w.pe, x, xb, T);
     PKV_TRY(hipGetLastError());
     for (int li = 0; li < c.n_enc_layers; ++li) {
       const EncoderLayerWeights& e = w.enc[li];
-      EpiArgs eq = {e.in_b, nullptr, nullptr, nullptr, qk, vt};
-      PKV_TRY(launch_gemm<kEpiQkv>(xb, kDT, e.in_w, T, 3 * kDT, kDT, eq, stream));
+      EpiArgs eq = {e.in_b, nullptr, nullptr, qk};
+      PKV_TRY(launch_gemm<kEpiBiasH>(xb, kDT, e.in_w, T, 3 * kDT, kDT, eq, n_cu, stream));
+      v_transpose_kernel<<<dim3(kWin / 64, kHeads, (unsigned)n_win), 256, 0, stream>>>(qk, vt, T);
+      PKV_TRY(hipGetLastError());
       window_attention_kernel<<<dim3(kWin / 256, kHeads, (unsigned)n_win), 256, 0, stream>>>(qk, vt, ao, T, (int)n_win);
       PKV_TRY(hipGetLastError());
-      EpiArgs eo = {e.out_b, nullptr, x, tmp, nullptr, nullptr};
-      PKV_TRY(launch_gemm<kEpiBiasResidF32>(ao, kDT, e.out_w, T, kDT, kDT, eo, stream));
+      EpiArgs eo = {e.out_b, nullptr, tmp, nullptr};
+      PKV_TRY(launch_gemm<kEpiBiasF32>(ao, kDT, e.out_w, T, kDT, kDT, eo, n_cu, stream));
       layernorm_kernel<<<(unsigned)((T + 3) / 4), 256, 0, stream>>>(tmp, e.ln1_g, e.ln1_b, x, xb, T);
       PKV_TRY(hipGetLastError());
-      EpiArgs e1 = {e.ffn1_b, nullptr, nullptr, nullptr, hid, nullptr};
-      PKV_TRY(launch_gemm<kEpiBiasReluH>(xb, kDT, e.ffn1_w, T, c.d_ffn, kDT, e1, stream));
-      EpiArgs ef = {e.ffn2_b, nullptr, x, tmp, nullptr, nullptr};
-      PKV_TRY(launch_gemm<kEpiBiasResidF32>(hid, c.d_ffn, e.ffn2_w, T, kDT, c.d_ffn, ef, stream));
+      EpiArgs e1 = {e.ffn1_b, nullptr, nullptr, hid};
+      PKV_TRY(launch_gemm<kEpiBiasReluH>(xb, kDT, e.ffn1_w, T, c.d_ffn, kDT, e1, n_cu, stream));
+      EpiArgs ef = {e.ffn2_b, nullptr, tmp, nullptr};
+      PKV_TRY(launch_gemm<kEpiBiasF32>(hid, c.d_ffn, e.ffn2_w, T, kDT, c.d_ffn, ef, n_cu, stream));
       layernorm_kernel<<<(unsigned)((T + 3) / 4), 256, 0, stream>>>(tmp, e.ln2_g, e.ln2_b, x, xb, T);
       PKV_TRY(hipGetLastError());
     }
@@ -566,12 +721,12 @@ hipError_t mapper_forward(proxykv_ctx* ctx, const float* x_in, int64_t N, float*
     PKV_TRY(hipGetLastError());
 
     // stage 3
-    const int nkv = 2 * c.H_kv * c.d_head_x;
-    EpiArgs e3 = {w.kv_b, nullptr, nullptr, kv3, nullptr, nullptr};
-    PKV_TRY(launch_gemm<kEpiBiasF32>(zg, kDT, w.kv_w, N, nkv, kDT, e3, stream));
+    const int nkv = kv3_stride(c);
+    EpiArgs e3 = {w.kv_b, nullptr, kv3, nullptr};
+    PKV_TRY(launch_gemm<kEpiBiasF32>(zg, kDT, w.kv_w, N, nkv, kDT, e3, n_cu, stream));
     const int tok_per_block = 256 / c.H_l;
     stage3_kernel<<<(unsigned)((N + tok_per_block - 1) / tok_per_block), 256, 0, stream>>>(
-        kv3, w.queries, w.out_w, w.out_b, yhat, N, c.H_kv, c.H_l, ll, ll_hi);
+        kv3, w.queries, w.out_w, w.out_b, yhat, N, c.H_kv, c.H_l, nkv, ll, ll_hi);
     PKV_TRY(hipGetLastError());
     ll = ll_hi;
   }
