@@ -13,6 +13,7 @@ from .proxykv_oracle import (  # noqa: F401
     score,
     score_unit,
     softmax_rows_unit,
+    softmax_row,
     stem,
     positional_encoding,
     encoder_layer,

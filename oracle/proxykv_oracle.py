@@ -121,6 +121,26 @@ def softmax_rows_unit(q: torch.Tensor, k_ctx: torch.Tensor, k_rec: torch.Tensor,
     return ea / Z, eb / Z
 
 
+def softmax_row(q_i: torch.Tensor, k_ctx: torch.Tensor, k_rec_prefix: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
+    """The attention probabilities of ONE reconstruction query (Sec. 3, system
+    overview: Softmax(q K^T / sqrt(D)) over the keys the query sees).
+
+    q_i [d]; k_ctx [N, d] all context keys; k_rec_prefix [len, d] the
+    reconstruction keys of the query's own chunk from the chunk's first token up
+    to and including the query itself (len >= 1).  Returns (p_ctx [N], p_rec
+    [len]); the two together sum to one.  This is one row of
+    `softmax_rows_unit`, for checks at sizes where the whole matrix is too large.
+    """
+    q_i, k_ctx, k_rec_prefix = q_i.to(F64), k_ctx.to(F64), k_rec_prefix.to(F64)
+    d = q_i.shape[0]
+    a = (k_ctx @ q_i) / math.sqrt(d)
+    b = (k_rec_prefix @ q_i) / math.sqrt(d)
+    top = torch.maximum(a.max(), b.max())
+    ea, eb = torch.exp(a - top), torch.exp(b - top)
+    Z = ea.sum() + eb.sum()
+    return ea / Z, eb / Z
+
+
 def score_unit(q: torch.Tensor, k_ctx: torch.Tensor, k_rec: torch.Tensor, chunk: int,
                reduce: str = "max", max_block_bytes: int = 1 << 29) -> torch.Tensor:
     """Score of the N context keys of one (proxy layer, KV head).

@@ -11,7 +11,8 @@
 // With c = log2(e) / sqrt(d) the probability is p = 2^(c*s - L2), L2 the row's log2-sum-exp2.
 // Pass 1 stores -L2 / c per query row; it is fed to the MFMA as the accumulator's initial value,
 // so tiles come out as s - L2/c and need nothing but a running maximum (v_max3); one exp2 per
-// context key is taken at the very end (max and exp commute).
+// context key is taken at the very end (max and exp commute).  The result is a probability: rounding in
+// s - L2/c can carry it a few ulp past one, so it is clamped to one.
 //
 // Streaming: three LDS buffers and one barrier per tile.  While tile t is computed, tile t+2 goes
 // from registers to LDS and tile t+3 is fetched from global memory into registers, all issued
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(256, 2) void score_colmax_kernel(const uint16_t* __
 #pragma unroll
   for (int cs = 0; cs < NCOL; ++cs) {
     const float m = __builtin_fmaxf(runmax[cs], swap_halves(runmax[cs]));
-    if (half == 0 && kn[cs] < N) x[(size_t)(l * H_kv + hs) * N + kn[cs]] = __builtin_amdgcn_exp2f(c * m);
+    if (half == 0 && kn[cs] < N) x[(size_t)(l * H_kv + hs) * N + kn[cs]] = __builtin_fminf(__builtin_amdgcn_exp2f(c * m), 1.0f);
   }
 }
 

@@ -1,0 +1,214 @@
+"""GPU parity at the workloads' full sizes, in the launch configuration bench.py times (one
+proxykv_prune over all layers), on outputs the CPU oracle can compute one by one.
+
+Every oracle input comes from the seeded generator (synth), never from the HIP path:
+  * scoring  - one whole (proxy layer, KV head) unit exactly where that takes seconds; on every
+               workload the planted heavy hitters (their source query's softmax row is one matrix-vector
+               product; the score lies between that probability and 1) and, for sampled queries at chunk
+               starts, chunk ends and the ragged tail, the bound X[n] >= p_i(n) on all N keys at once;
+  * mapper   - proxykv_map on a seeded score-like X of the full shape, against the oracle on sampled spans
+               (two adjacent windows pin a fully averaged 1024-token span; the first and last windows pin
+               the singly covered ends and the ragged tail) for every target layer paired with the sampled
+               proxy layer;
+  * top-k    - proxykv_topk on a seeded array of the full shape, every row, bit-exact;
+  * compact  - proxykv_compact on the full target cache, sampled (layer, head) rows, bit-exact.
+The fused call is then tied to the stage calls: on the same inputs it returns the same bits as
+score -> map -> top-k -> compact called one by one.
+Floating point: |gpu - ref| <= 2e-3 + 1e-2 |ref|.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_16360_amd import binding as pk
+from paper_2605_16360_amd import synth
+
+pytestmark = pytest.mark.gpu
+ATOL, RTOL = 2e-3, 1e-2
+
+
+def _close(g: torch.Tensor, r: torch.Tensor, what: str):
+    g, r = g.detach().double().cpu(), r.double()
+    assert g.shape == r.shape, (what, g.shape, r.shape)
+    assert bool(torch.isfinite(g).all()), f"{what}: non-finite values"
+    err = (g - r).abs()
+    bound = ATOL + RTOL * r.abs()
+    worst = int(torch.argmax(err - bound))
+    assert bool((err <= bound).all()), (f"{what}: max abs err {float(err.max()):.3e}, worst at flat {worst}: "
+                                        f"gpu {float(g.flatten()[worst])} ref {float(r.flatten()[worst])}")
+
+
+def _sample_queries(case, rng, n_extra=2):
+    """Query indices at chunk starts, chunk ends, the ragged tail and a few random places."""
+    qs = {0, min(case.chunk, case.N_q) - 1, case.N_q - 1, ((case.N_q - 1) // case.chunk) * case.chunk}
+    if case.N_q > case.chunk:
+        qs |= {case.chunk, 2 * case.chunk - 1 if case.N_q >= 2 * case.chunk else case.N_q - 1}
+    qs |= {int(v) for v in rng.integers(0, case.N_q, size=n_extra)}
+    return sorted(qs)
+
+
+def _check_scores(case, x_gpu, q, kc, kr, units, full_unit=None):
+    """x_gpu [L_s, H_kv, N] on the GPU; q, kc, kr the (GPU) bf16 inputs.  `units` = (layer, KV head) pairs
+    checked through planted keys and row bounds; `full_unit` one pair compared key by key."""
+    G, N = case.G, case.N
+    plan = synth.plant_plan(case)
+    rng = np.random.default_rng(5)
+    x_min, x_max = float(x_gpu.min()), float(x_gpu.max())
+    assert x_min >= 0.0 and x_max <= 1.0, (x_min, x_max)
+    for (l, h) in units:
+        kc_u, kr_u = kc[l, h].double().cpu(), kr[l, h].double().cpu()
+        xg = x_gpu[l, h].double().cpu()
+        # planted heavy hitters: p of the source query's row <= X <= 1
+        n_pl = min(case.n_planted, 24)
+        for j in range(n_pl):
+            pos, g, i = int(plan["pos"][l, h, j]), int(plan["g"][l, h, j]), int(plan["i"][l, h, j])
+            lo = (i // case.chunk) * case.chunk
+            p_ctx, _ = oracle.softmax_row(q[l, h * G + g, i].double().cpu(), kc_u, kr_u[lo:i + 1])
+            p = float(p_ctx[pos])
+            assert p > 0.5, "the planted key does not dominate its source row"
+            assert float(xg[pos]) >= p - (ATOL + RTOL * p), (l, h, pos, float(xg[pos]), p)
+            if p > 1.0 - 1e-3:  # then [p, 1] pins the score itself
+                assert abs(float(xg[pos]) - p) <= ATOL + RTOL * p
+        # sampled rows: the score of every key is at least that row's probability
+        for g in sorted({0, G - 1}):
+            for i in _sample_queries(case, rng):
+                lo = (i // case.chunk) * case.chunk
+                p_ctx, _ = oracle.softmax_row(q[l, h * G + g, i].double().cpu(), kc_u, kr_u[lo:i + 1])
+                slack = ATOL + RTOL * p_ctx
+                bad = xg < p_ctx - slack
+                assert not bool(bad.any()), (l, h, g, i, int(bad.nonzero()[0]))
+    if full_unit is not None:
+        l, h = full_unit
+        ref = oracle.score_unit(q[l, h * G:(h + 1) * G].double().cpu(), kc[l, h].double().cpu(), kr[l, h].double().cpu(),
+                                case.chunk)
+        _close(x_gpu[l, h], ref, f"score[{case.name}] unit ({l}, {h})")
+
+
+def _score_like(shape, seed):
+    """Seeded stand-in for a score tensor: mostly small positive values, a few near one."""
+    u = synth.normal_tensor(shape, seed, 31, device="cuda")
+    return (torch.sigmoid(1.5 * u) ** 8).contiguous()
+
+
+def _oracle_span(X_l, w, a, b, win=2048, stride=1024):
+    """Oracle Y_hat[:, a:b] of one proxy layer's scores X_l [H_s, N] (CPU fp64): the stem on the span
+    plus the reach of the windows that cover it, those windows' encoder passes, their average, stage 3."""
+    N = X_l.shape[1]
+    spans = [(s, e) for (s, e) in oracle.window_spans(N, win, stride) if s < b and e > a]
+    lo, hi = min(s for s, _ in spans), max(e for _, e in spans)
+    s0, s1 = max(0, lo - 2), min(N, hi + 2)          # two k = 3 convolutions reach two tokens each way
+    z = oracle.stem(X_l[:, s0:s1], w)                 # [s1 - s0, D]
+    # rows near a cut that is not the sequence's end are wrong within two tokens of it; they lie outside [lo, hi)
+    z_local = torch.full((N, z.shape[1]), math.nan, dtype=torch.float64)
+    z_local[lo:hi] = z[lo - s0:hi - s0]
+    zg = torch.zeros(b - a, z.shape[1], dtype=torch.float64)
+    cnt = torch.zeros(b - a, 1, dtype=torch.float64)
+    for (s, e) in spans:
+        out = oracle.encoder_window(z_local[s:e], w)
+        u0, u1 = max(a, s), min(b, e)
+        zg[u0 - a:u1 - a] += out[u0 - s:u1 - s]
+        cnt[u0 - a:u1 - a] += 1.0
+    return oracle.head_cross_attention(zg / cnt, w)   # [H_l, b - a]
+
+
+def _check_mapper(case, ctx, w, samples):
+    """samples: (proxy layer, a, b) spans."""
+    X = _score_like((case.L_s, case.H_kv, case.N), 41)
+    y = pk.proxykv_map(ctx, X)
+    torch.cuda.synchronize()
+    pairing = pk.proxykv_layer_pairing(ctx.cfg)
+    for (ls, a, b) in samples:
+        ref = _oracle_span(X[ls].double().cpu(), w, a, b)
+        targets = [ll for ll in range(case.L_l) if pairing[ll] == ls]
+        assert targets
+        for ll in targets:
+            _close(y[ll, :, a:b], ref, f"map[{case.name}] proxy layer {ls} -> target layer {ll}, tokens [{a}, {b})")
+    return X, y
+
+
+def _check_topk_compact(case, ctx, keep_ratio, rows_sampled=6):
+    N, rows = case.N, case.L_l * case.H_l
+    K = pk.proxykv_keep_count(N, keep_ratio)
+    assert K == oracle.keep_count(N, keep_ratio)
+    s = synth.normal_tensor((rows, N), 9, 51, device="cuda")
+    s[1] = torch.round(s[1] * 8) / 8                   # heavy ties
+    s[2] = 0.25                                        # all equal
+    idx = pk.proxykv_topk(ctx, s, K)
+    torch.cuda.synchronize()
+    ref = oracle.topk(s.cpu(), K)
+    assert torch.equal(idx.cpu(), ref), f"top-k[{case.name}] differs"
+    k_t, v_t = synth.make_target_kv(case, device="cuda")
+    idx_l = ref.view(case.L_l, case.H_l, K).cuda()
+    k_out, v_out = pk.proxykv_compact(ctx, k_t, v_t, idx_l)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(11)
+    picks = {(0, 0), (case.L_l - 1, case.H_l - 1)} | {(int(rng.integers(case.L_l)), int(rng.integers(case.H_l)))
+                                                       for _ in range(rows_sampled - 2)}
+    for (l, h) in sorted(picks):
+        for src, out in ((k_t, k_out), (v_t, v_out)):
+            exp = oracle.compact(src[l:l + 1, h:h + 1].cpu(), idx_l[l:l + 1, h:h + 1].cpu())
+            assert torch.equal(out[l:l + 1, h:h + 1].cpu().view(torch.int16), exp.view(torch.int16)), (case.name, l, h)
+    return k_t, v_t
+
+
+def _check_fused_equals_stages(case, ctx, q, kc, kr, k_t, v_t, keep_ratio):
+    """proxykv_prune against the stage entry points called one by one on the same inputs: same bits."""
+    dev = "cuda"
+    x = torch.empty(case.L_s, case.H_kv, case.N, dtype=torch.float32, device=dev)
+    y = torch.empty(case.L_l, case.H_l, case.N, dtype=torch.float32, device=dev)
+    k_out, v_out, idx, K = pk.proxykv_prune(ctx, q, kc, kr, case.chunk, keep_ratio, k_t, v_t, x_out=x, yhat_out=y)
+    torch.cuda.synchronize()
+    x2 = pk.proxykv_score(ctx, q, kc, kr, case.chunk)
+    y2 = pk.proxykv_map(ctx, x2)
+    idx2 = pk.proxykv_topk(ctx, y2.view(-1, case.N), K).view(case.L_l, case.H_l, K)
+    k2, v2 = pk.proxykv_compact(ctx, k_t, v_t, idx2)
+    torch.cuda.synchronize()
+    assert torch.equal(x, x2) and torch.equal(y, y2) and torch.equal(idx, idx2)
+    assert torch.equal(k_out.view(torch.int16), k2.view(torch.int16)) and torch.equal(v_out.view(torch.int16), v2.view(torch.int16))
+    assert bool((idx[..., 1:] > idx[..., :-1]).all()) and int(idx.min()) >= 0 and int(idx.max()) < case.N
+    return x
+
+
+def _run_case(name, units, full_unit, map_samples, keep_ratio=0.3):
+    case = synth.CASES[name]
+    w = synth.make_mapper_weights(case.H_kv, case.H_l)
+    ctx = pk.proxykv_create(pk.config_for_case(case))
+    pk.proxykv_set_mapper_weights(ctx, w)
+    pk.proxykv_reserve(ctx, case.N, case.N_q)
+    _check_mapper(case, ctx, w, map_samples)
+    k_t, v_t = _check_topk_compact(case, ctx, keep_ratio)
+    q, kc, kr = synth.make_proxy_qk(case, device="cuda")
+    x = _check_fused_equals_stages(case, ctx, q, kc, kr, k_t, v_t, keep_ratio)
+    _check_scores(case, x, q, kc, kr, units, full_unit)
+    pk.proxykv_destroy(ctx)
+
+
+def test_llama_8k_full_size():
+    N = synth.CASES["llama_8k"].N
+    _run_case("llama_8k", units=[(0, 0), (7, 3), (15, 7)], full_unit=(9, 5),
+              map_samples=[(0, 0, 2048), (8, 3072, 4096), (15, N - 2048, N)])
+
+
+def test_llama_32k_full_size():
+    """The workload bench.py times."""
+    N = synth.CASES["llama_32k"].N
+    _run_case("llama_32k", units=[(0, 0), (15, 7)], full_unit=(6, 2),
+              map_samples=[(0, 0, 2048), (7, 16384, 17408), (15, N - 2048, N)])
+
+
+def test_qwen32b_32k_full_size():
+    """Head dimension 128, groups of 6, chunks of 4096, 64 target layers paired with 28 proxy layers."""
+    N = synth.CASES["qwen32b_32k"].N
+    _run_case("qwen32b_32k", units=[(0, 0), (13, 1), (27, 1)], full_unit=None,
+              map_samples=[(0, 0, 1024), (27, N - 1024, N)], keep_ratio=0.5)
+
+
+def test_qwen_170k_full_size():
+    """N = 170000: ragged key tiles, a last chunk of 16 queries, 166 windows with a short tail, rows longer
+    than the top-k kernel can hold in LDS."""
+    N = synth.CASES["qwen_170k"].N
+    _run_case("qwen_170k", units=[(0, 0), (23, 1)], full_unit=None,
+              map_samples=[(0, 0, 1024), (11, 84992, 86016), (23, N - 1024, N)])

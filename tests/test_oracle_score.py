@@ -51,6 +51,20 @@ def test_score_unit_matches_brute_force(G, N, N_q, chunk, d):
     np.testing.assert_allclose(Xs.numpy(), ref_s, rtol=1e-12)
 
 
+def test_softmax_row_matches_brute_force_rows():
+    """The single-row form against the per-row Python loops, at chunk starts, inside chunks and at
+    the ragged last chunk."""
+    N, N_q, chunk, d = 10, 11, 4, 6
+    q, kc, kr = _rand((N_q, d), 14), _rand((N, d), 15), _rand((N_q, d), 16)
+    P, R = _brute_rows(q.numpy(), kc.numpy(), kr.numpy(), chunk)
+    for i in (0, 3, 4, 6, 8, 10):
+        lo = (i // chunk) * chunk
+        p_ctx, p_rec = oracle.softmax_row(q[i], kc, kr[lo:i + 1])
+        np.testing.assert_allclose(p_ctx.numpy(), P[i], rtol=1e-12, atol=1e-16)
+        np.testing.assert_allclose(p_rec.numpy(), R[i, lo:i + 1], rtol=1e-12, atol=1e-16)
+        assert abs(float(p_ctx.sum() + p_rec.sum()) - 1.0) < 1e-12
+
+
 def test_softmax_rows_match_library_softmax_on_masked_matrix():
     N, N_q, chunk, d = 11, 9, 4, 8
     q, kc, kr = _rand((N_q, d), 4), _rand((N, d), 5), _rand((N_q, d), 6)
