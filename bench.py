@@ -27,6 +27,18 @@ def bytes_topk_compact(case, K):
     return topk, compact
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this workload
+    (two --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by a 1 GiB copy); None if there is none."""
+    import os
+    import re
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"prune_{workload}_hbm_counters.md")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"traffic_bytes_per_launch\[%s_kernel\] = ([0-9.eE+-]+)" % re.escape(kernel), open(path).read())
+    return float(m.group(1)) if m else None
+
+
 def cpu_baseline(case, keep_ratio, x_layer0):
     """Times the CPU oracle on a bounded sample of the same workload and scales each stage linearly
     to the full problem.  x_layer0: [H_kv, N] fp32 CPU tensor (one proxy layer's scores) used as the
@@ -83,6 +95,9 @@ def main():
     ap.add_argument("--case", default="llama_32k")
     ap.add_argument("--keep-ratio", type=float, default=0.3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-copy", action="store_true",
+                    help="after the timed steps, copy 1 GiB device to device with a plain torch copy kernel: the "
+                         "known-size dispatch that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -97,8 +112,14 @@ def main():
         sys.exit(3)
     case = synth.CASES[args.case]
     dev = torch.device("cuda:0")
+
+    def note(msg):   # progress on stderr for runs under a profiler, where every dispatch is slow
+        if args.pmc_copy:
+            print(f"bench.py: {msg}", file=sys.stderr, flush=True)
     q, kc, kr = synth.make_proxy_qk(case, device=dev)
+    note("proxy Q/K generated")
     k_t, v_t = synth.make_target_kv(case, device=dev)
+    note("target K/V generated")
     w = synth.make_mapper_weights(case.H_kv, case.H_l)
     ctx = pk.proxykv_create(pk.config_for_case(case))
     pk.proxykv_set_mapper_weights(ctx, w)
@@ -119,13 +140,23 @@ def main():
     torch.cuda.synchronize()
     stage_ms = {s: 0.0 for s in pk.STAGES}
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for i in range(args.steps):
         step()
+        note(f"step {i} enqueued")
         for s, v in pk.proxykv_profile_read(ctx).items():   # HIP events recorded on the work stream
             stage_ms[s] += v / args.steps
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
+
+    if args.pmc_copy:
+        src = torch.arange(1 << 28, dtype=torch.int32, device=dev)   # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        note("calibration copy done")
 
     f_lse, f_col = flops_score(case)
     kern = {"score_lse": f_lse, "score_colmax": f_col}
@@ -142,7 +173,7 @@ def main():
         "config": {"workload": case.name, "N": case.N, "N_q": case.N_q, "chunk": case.chunk, "keep_ratio": args.keep_ratio,
                    "K": K, "proxy": [case.L_s, case.H_q, case.H_kv, case.d], "target": [case.L_l, case.H_l, case.D]},
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": achieved, "peak": peak_tflops, "unit": "TFLOP/s",
-                     "frac": achieved / peak_tflops, "traffic": None},
+                     "frac": achieved / peak_tflops, "traffic": measured_traffic(case.name, dominant)},
         "stages_ms": stage_ms,
         "score_mfma_frac": (f_lse + f_col) / ((stage_ms["score_lse"] + stage_ms["score_colmax"]) * 1e-3) / 1e12 / peak_tflops,
         "topk_compact_hbm": {"bytes": b_topk + b_comp, "achieved": hbm_gbps, "peak": 8000.0, "unit": "GB/s",
