@@ -398,18 +398,40 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict_
 // Window attention (8 heads x 64, full bidirectional attention inside each window).
 // Computes S^T = K Q^T so that a lane owns one query column; P^T then feeds the second MFMA as its
 // B operand straight from the accumulator registers, with V^T tiles as the A operand.
-// grid (2048 / 256, 8 heads, n_win), 256 threads; wave owns 64 queries.
+// 256 threads; a workgroup owns 256 queries of one (window, head), a wave 64 of them (two 32-column
+// sub-tiles); keys stream in tiles of 64 through three LDS stages (K tile + V^T tile, 16 KB each) with one
+// barrier per tile: while tile t is computed, tile t+2 goes from registers to LDS and tile t+3 is
+// fetched from global memory.
+// Online softmax with a lazily raised reference: a column's reference only moves when a logit exceeds it
+// by more than 2^8, so the rescaling of the output accumulators is rare; probabilities stay below 2^8,
+// which half holds with its full relative precision.
+// Block -> work mapping: blocks are dealt round-robin to the 8 XCDs, so block b takes q-block (b / 8) % 8
+// of item (b / 64) * 8 + b % 8: the 8 q-blocks of one (window, head) run on one XCD and share its L2 copy of
+// that head's K and V.
 // ------------------------------------------------------------------------------------------
+constexpr float kAttnLazy = 8.0f;
+
+// max over the 32 elements of two accumulator tiles (v_max3 tree)
+__device__ __forceinline__ float max16_8(const f32x16& a, const f32x16& b) {
+  float m = max3f(a[0], a[1], a[2]);
+#pragma unroll
+  for (int r = 3; r < 15; r += 2) m = max3f(m, a[r], a[r + 1]);
+  m = max3f(m, a[15], b[0]);
+#pragma unroll
+  for (int r = 1; r < 15; r += 2) m = max3f(m, b[r], b[r + 1]);
+  return __builtin_fmaxf(m, b[15]);
+}
+
 __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t* __restrict__ qk,
                                                                    const uint16_t* __restrict__ vt,
                                                                    uint16_t* __restrict__ ao, int64_t T, int n_win) {
-  __shared__ u32x4 lds_k[64 * 8];
-  __shared__ u32x4 lds_v[64 * 8];
+  __shared__ u32x4 lds[3 * 1024];  // stage = K tile (64 keys x 8 chunks) then V^T tile (64 d rows x 8 chunks)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
-  const int hd = blockIdx.y, wk = blockIdx.z;
+  const int bj = blockIdx.x >> 3, item = (bj >> 3) * kXcds + (blockIdx.x & 7);
+  const int wk = item / kHeads, hd = item % kHeads;
   const int64_t base = (int64_t)wk * kWin;
   const int len = (wk < n_win - 1) ? kWin : (int)(T - base);
-  const int i0 = blockIdx.x * 256;
+  const int i0 = (bj & 7) * 256;
   if (i0 >= len) return;
   constexpr float c = 1.4426950408889634f * 0.125f;  // log2(e) / sqrt(64)
 
@@ -427,65 +449,83 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
 #pragma unroll
   for (int ds = 0; ds < 2; ++ds)
 #pragma unroll
-    for (int cs = 0; cs < 2; ++cs)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[ds][cs][r] = 0.0f;
+    for (int cs = 0; cs < 2; ++cs) o[ds][cs] = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   float m_run[2] = {-1.0e30f, -1.0e30f}, l_run[2] = {0.0f, 0.0f};
 
   const uint16_t* kbase = qk + (size_t)base * (3 * kDT) + kDT + hd * 64;
   const uint16_t* vbase = vt + (size_t)(wk * kHeads + hd) * 64 * kWin;
+  const int n_tiles = (len + 63) / 64;
+  // staging: thread moves chunk tid % 8 of rows tid / 8 and tid / 8 + 32 of both tiles
+  const int srow = tid >> 3, sch = tid & 7;
+  const int sslot = srow * 8 + (sch ^ swz8(srow));  // swz8(srow + 32) == swz8(srow)
   u32x4 rk[2], rv[2];
-  auto fetch = [&](int j0) {
+  auto fetch = [&](int t) {
+    const int j0 = t * 64;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const int id = tid + 256 * i, row = id >> 3, ch = id & 7;
+      const int row = srow + 32 * i;
       int j = j0 + row;
       j = j < len ? j : len - 1;
-      rk[i] = *reinterpret_cast<const u32x4*>(kbase + (size_t)j * (3 * kDT) + ch * 8);
-      rv[i] = *reinterpret_cast<const u32x4*>(vbase + (size_t)row * kWin + j0 + ch * 8);
+      rk[i] = *reinterpret_cast<const u32x4*>(kbase + (size_t)j * (3 * kDT) + sch * 8);
+      rv[i] = *reinterpret_cast<const u32x4*>(vbase + (size_t)row * kWin + j0 + sch * 8);
+    }
+  };
+  auto store = [&](int t) {
+    u32x4* st = lds + (t % 3) * 1024;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      st[sslot + 32 * 8 * i] = rk[i];
+      st[512 + sslot + 32 * 8 * i] = rv[i];
     }
   };
   fetch(0);
-  for (int j0 = 0; j0 < len; j0 += 64) {
+  store(0);
+  if (n_tiles > 1) {
+    fetch(1);
+    store(1);
+  }
+  if (n_tiles > 2) fetch(2);
+  const int fsw = swz8(l32);
+
+  for (int t = 0; t < n_tiles; ++t) {
+    // every wave has finished tile t-1: its stage takes tile t+2, the registers take tile t+3
     __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int id = tid + 256 * i, row = id >> 3, ch = id & 7;
-      lds_k[row * 8 + (ch ^ swz8(row))] = rk[i];
-      lds_v[row * 8 + (ch ^ swz8(row))] = rv[i];
-    }
-    __syncthreads();
-    if (j0 + 64 < len) fetch(j0 + 64);
+    if (t + 2 < n_tiles) store(t + 2);
+    if (t + 3 < n_tiles) fetch(t + 3);
+    const u32x4* st = lds + (t % 3) * 1024;
+    const int j0 = t * 64;
     const bool ragged = j0 + 64 > len;
+
+    // S^T tiles of both query sub-tiles: s[cs][ks] = K[ks] Q[cs]^T
+    f32x16 s[2][2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      f16x8 fk[4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) fk[kk] = as_f16x8(st[(ks * 32 + l32) * 8 + ((kk * 2 + half) ^ fsw)]);
+#pragma unroll
+      for (int cs = 0; cs < 2; ++cs) {
+        f32x16 acc = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) acc = mfma_f16_32x32x16(fk[kk], bq[cs][kk], acc);
+        s[cs][ks] = acc;
+      }
+    }
 #pragma unroll
     for (int cs = 0; cs < 2; ++cs) {
-      f32x16 s[2];
+      if (ragged) {
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[ks][r] = 0.0f;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          const int row = ks * 32 + l32;
-          const f16x8 fk = as_f16x8(lds_k[row * 8 + ((kk * 2 + half) ^ swz8(row))]);
-          s[ks] = mfma_f16_32x32x16(fk, bq[cs][kk], s[ks]);
-        }
-        if (ragged) {
+        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int j = j0 + ks * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-            s[ks][r] = j < len ? s[ks][r] : kNegInf;
+            s[cs][ks][r] = j < len ? s[cs][ks][r] : kNegInf;
           }
-        }
       }
-      float tmax = kNegInf;
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) tmax = max3f(tmax, s[ks][r], s[ks][r + 1]);
+      float tmax = max16_8(s[cs][0], s[cs][1]);
       tmax = __builtin_fmaxf(tmax, swap_halves(tmax)) * c;
-      if (__builtin_amdgcn_ballot_w64(tmax > m_run[cs])) {
-        const float nm = __builtin_fmaxf(m_run[cs], tmax);
+      if (__builtin_amdgcn_ballot_w64(tmax > m_run[cs] + kAttnLazy)) {
+        const float nm = tmax > m_run[cs] + kAttnLazy ? tmax : m_run[cs];
         const float alpha = __builtin_amdgcn_exp2f(m_run[cs] - nm);
         l_run[cs] *= alpha;
 #pragma unroll
@@ -495,45 +535,56 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
         m_run[cs] = nm;
       }
       const float nref = -m_run[cs];
-      float lsum = 0.0f;
+      float l0 = 0.0f, l1 = 0.0f;
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
         for (int u2 = 0; u2 < 2; ++u2) {
           f32x8 p;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[ks][u2 * 8 + e], c, nref));
-            lsum += p[e];
+          for (int e = 0; e < 8; e += 2) {
+            p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[cs][ks][u2 * 8 + e], c, nref));
+            p[e + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[cs][ks][u2 * 8 + e + 1], c, nref));
+            l0 += p[e];
+            l1 += p[e + 1];
           }
           const f16x8 pb = __builtin_convertvector(p, f16x8);
           const int u = ks * 2 + u2;
 #pragma unroll
           for (int ds = 0; ds < 2; ++ds) {
-            const int row = ds * 32 + l32;  // V^T fragment: d row, 16-key step u
-            const f16x8 fv = as_f16x8(lds_v[row * 8 + ((u * 2 + half) ^ swz8(row))]);
+            const f16x8 fv = as_f16x8(st[512 + (ds * 32 + l32) * 8 + ((u * 2 + half) ^ fsw)]);  // V^T: d row, 16-key step u
             o[ds][cs] = mfma_f16_32x32x16(fv, pb, o[ds][cs]);
           }
         }
       }
-      l_run[cs] += lsum;
+      l_run[cs] += l0 + l1;
     }
   }
+
+  // output: O^T / row sum, through LDS so that every query row is written as 128 contiguous bytes
+  __syncthreads();
+  uint16_t* ot = reinterpret_cast<uint16_t*>(lds) + wave * (64 * 72);  // [64 queries][64 d + 8 pad] per wave
 #pragma unroll
   for (int cs = 0; cs < 2; ++cs) {
     const float inv = 1.0f / (l_run[cs] + swap_halves(l_run[cs]));
-    if (qi[cs] < len) {
-      uint16_t* dst = ao + (size_t)(base + qi[cs]) * kDT + hd * 64;
 #pragma unroll
-      for (int ds = 0; ds < 2; ++ds)
+    for (int ds = 0; ds < 2; ++ds)
 #pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-          f16x4 pk;
+      for (int rg = 0; rg < 4; ++rg) {
+        f16x4 pk;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) pk[e] = (_Float16)(o[ds][cs][rg * 4 + e] * inv);
-          *reinterpret_cast<f16x4*>(dst + ds * 32 + rg * 8 + half * 4) = pk;
-        }
-    }
+        for (int e = 0; e < 4; ++e) pk[e] = (_Float16)(o[ds][cs][rg * 4 + e] * inv);
+        *reinterpret_cast<f16x4*>(ot + (cs * 32 + l32) * 72 + ds * 32 + rg * 8 + half * 4) = pk;
+      }
+  }
+  // the wave reads back its own rows only: no barrier needed beyond the wave's own LDS ordering
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int id = lane + 64 * i, row = id >> 3, ch = id & 7;  // 64 rows x 8 chunks of 16 bytes
+    const int q = i0 + wave * 64 + row;
+    if (q < len)
+      *reinterpret_cast<u32x4*>(ao + (size_t)(base + q) * kDT + hd * 64 + ch * 8) =
+          *reinterpret_cast<const u32x4*>(ot + row * 72 + ch * 8);
   }
 }
 
@@ -704,7 +755,7 @@ hipError_t mapper_forward(proxykv_ctx* ctx, const float* x_in, int64_t N, float*
       PKV_TRY(launch_gemm<kEpiBiasH>(xb, kDT, e.in_w, T, 3 * kDT, kDT, eq, n_cu, stream));
       v_transpose_kernel<<<dim3(kWin / 64, kHeads, (unsigned)n_win), 256, 0, stream>>>(qk, vt, T);
       PKV_TRY(hipGetLastError());
-      window_attention_kernel<<<dim3(kWin / 256, kHeads, (unsigned)n_win), 256, 0, stream>>>(qk, vt, ao, T, (int)n_win);
+      window_attention_kernel<<<(unsigned)(n_win * kHeads * (kWin / 256)), 256, 0, stream>>>(qk, vt, ao, T, (int)n_win);
       PKV_TRY(hipGetLastError());
       EpiArgs eo = {e.out_b, nullptr, tmp, nullptr};
       PKV_TRY(launch_gemm<kEpiBiasF32>(ao, kDT, e.out_w, T, kDT, kDT, eo, n_cu, stream));
