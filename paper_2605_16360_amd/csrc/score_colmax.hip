@@ -34,7 +34,7 @@ namespace {
 // VALU reduces the accumulators of pair i-1 (also across tile boundaries).
 // ---------------------------------------------------------------------------------------------
 template <int D, int NCOL>
-__global__ __launch_bounds__(256, 2) void score_colmax_kernel(const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(256, D == 128 ? 1 : 2) void score_colmax_kernel(const uint16_t* __restrict__ q,
                                                                const uint16_t* __restrict__ k_ctx,
                                                                const float* __restrict__ neg_lse,
                                                                float* __restrict__ x, int H_q, int G, int N, int N_q,
