@@ -190,18 +190,13 @@ hipError_t launch_score_lse(const uint16_t* q, const uint16_t* k_ctx, const uint
                             hipStream_t stream) {
   const int G = H_q / H_kv;
   const float c = 1.4426950408889634f / sqrtf((float)d), inv_c = 1.0f / c;
-#ifndef PKV_LSE_NCOL
-#define PKV_LSE_NCOL 2
-#endif
-#ifndef PKV_LSE_MINB
-#define PKV_LSE_MINB 2
-#endif
-  constexpr int NCOL = PKV_LSE_NCOL;
+  // two column sub-tiles per wave; the launch bound is a floor: at 158 registers three workgroups share a CU
+  constexpr int NCOL = 2, MINB = 2;
   dim3 grid((unsigned)((N_q + 128 * NCOL - 1) / (128 * NCOL)), (unsigned)H_q, (unsigned)L_s);
   if (d == 64)
-    score_lse_kernel<64, NCOL, PKV_LSE_MINB><<<grid, 256, 0, stream>>>(q, k_ctx, k_rec, neg_lse, H_q, G, (int)N, (int)N_q, chunk, c, inv_c);
+    score_lse_kernel<64, NCOL, MINB><<<grid, 256, 0, stream>>>(q, k_ctx, k_rec, neg_lse, H_q, G, (int)N, (int)N_q, chunk, c, inv_c);
   else
-    score_lse_kernel<128, NCOL, PKV_LSE_MINB><<<grid, 256, 0, stream>>>(q, k_ctx, k_rec, neg_lse, H_q, G, (int)N, (int)N_q, chunk, c, inv_c);
+    score_lse_kernel<128, NCOL, MINB><<<grid, 256, 0, stream>>>(q, k_ctx, k_rec, neg_lse, H_q, G, (int)N, (int)N_q, chunk, c, inv_c);
   return hipGetLastError();
 }
 
