@@ -28,6 +28,9 @@ namespace {
 
 // A chain's sum outside [0, kRebase) makes its lanes take a new reference.
 constexpr float kRebase = 1.8446744e19f;  // 2^64
+// Interior tiles are summed without any check; a column's running sum outside [0, kTileRedo) afterwards
+// undoes the tile and sums it again chain by chain with the check.
+constexpr float kTileRedo = 1.2676506e30f;  // 2^100
 
 template <int D, int NCOL, int MINB>
 __global__ __launch_bounds__(256, MINB) void score_lse_kernel(const uint16_t* __restrict__ q,
@@ -105,6 +108,40 @@ __global__ __launch_bounds__(256, MINB) void score_lse_kernel(const uint16_t* __
     lsum[cs] += sum;
   };
 
+  // sum of one chain, no check: 16 x (fma, exp2, add)
+  auto fast_sum = [&](const f32x16& acc, int cs) {
+    float s0 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[0], c, nref[cs]));
+    float s1 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[1], c, nref[cs]));
+    float s2 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[2], c, nref[cs]));
+    float s3 = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[3], c, nref[cs]));
+#pragma unroll
+    for (int r = 4; r < 16; r += 4) {
+      s0 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[r + 0], c, nref[cs]));
+      s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[r + 1], c, nref[cs]));
+      s2 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[r + 2], c, nref[cs]));
+      s3 += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[r + 3], c, nref[cs]));
+    }
+    return (s0 + s1) + (s2 + s3);
+  };
+  // the keys of an interior context tile, visible to every query, summed without checks
+  auto interior_tile = [&](const u32x4* buf) {
+#pragma unroll
+    for (int s = 0; s < C::SUB; ++s) {
+      bf16x8 a[C::KK];
+#pragma unroll
+      for (int kk = 0; kk < C::KK; ++kk) a[kk] = frag_read<D>(buf, s * 32 + l32, kk * 2 + half);
+      f32x16 acc[NCOL];
+#pragma unroll
+      for (int cs = 0; cs < NCOL; ++cs) {
+        acc[cs] = splat16(0.0f);
+#pragma unroll
+        for (int kk = 0; kk < C::KK; ++kk) acc[cs] = mfma_32x32x16(a[kk], b[cs][kk], acc[cs]);
+      }
+#pragma unroll
+      for (int cs = 0; cs < NCOL; ++cs) lsum[cs] += fast_sum(acc[cs], cs);
+    }
+  };
+
   fetch(0);
   tile_store<D>(regs, lds, tid);
   if (total > 1) {
@@ -121,25 +158,25 @@ __global__ __launch_bounds__(256, MINB) void score_lse_kernel(const uint16_t* __
     const u32x4* buf = lds + (t % kNBuf) * C::TILE_U4;
     const bool is_rec = t >= n_ctx;
     const int row0 = is_rec ? rec_lo + (t - n_ctx) * C::ROWS : t * C::ROWS;
-    if (!is_rec && row0 + C::ROWS <= N) {
-      // interior context tile: every key is visible to every query
+    // interior context tile: summed without checks, and again chain by chain with them if a sum went out of
+    // range (the very first tile does: the reference starts at -1e30)
+    bool careful = is_rec || row0 + C::ROWS > N;
+    if (!careful) {
+      float before[NCOL];
 #pragma unroll
-      for (int s = 0; s < C::SUB; ++s) {
-        bf16x8 a[C::KK];
+      for (int cs = 0; cs < NCOL; ++cs) before[cs] = lsum[cs];
+      interior_tile(buf);
+      bool bad = false;
 #pragma unroll
-        for (int kk = 0; kk < C::KK; ++kk) a[kk] = frag_read<D>(buf, s * 32 + l32, kk * 2 + half);
-        f32x16 acc[NCOL];
+      for (int cs = 0; cs < NCOL; ++cs) bad |= !(lsum[cs] < kTileRedo);
+      if (__builtin_amdgcn_ballot_w64(bad)) {
 #pragma unroll
-        for (int cs = 0; cs < NCOL; ++cs) {
-          acc[cs] = splat16(0.0f);
-#pragma unroll
-          for (int kk = 0; kk < C::KK; ++kk) acc[cs] = mfma_32x32x16(a[kk], b[cs][kk], acc[cs]);
-        }
-#pragma unroll
-        for (int cs = 0; cs < NCOL; ++cs) accumulate(acc[cs], cs);
+        for (int cs = 0; cs < NCOL; ++cs) lsum[cs] = before[cs];
+        careful = true;
       }
-    } else {
-      // ragged context tail, or a reconstruction tile where causality and chunk boundaries cut
+    }
+    if (careful) {
+      // ragged context tail, a reconstruction tile where causality and chunk boundaries cut, or a redo
       const int limit = is_rec ? i_end : N;
 #pragma unroll
       for (int s = 0; s < C::SUB; ++s) {
@@ -190,13 +227,13 @@ hipError_t launch_score_lse(const uint16_t* q, const uint16_t* k_ctx, const uint
                             hipStream_t stream) {
   const int G = H_q / H_kv;
   const float c = 1.4426950408889634f / sqrtf((float)d), inv_c = 1.0f / c;
-  // two column sub-tiles per wave; the launch bound is a floor: at 158 registers three workgroups share a CU
-  constexpr int NCOL = 2, MINB = 2;
+  // two column sub-tiles per wave; three workgroups per CU at d = 64 (at most 168 registers), two at d = 128
+  constexpr int NCOL = 2;
   dim3 grid((unsigned)((N_q + 128 * NCOL - 1) / (128 * NCOL)), (unsigned)H_q, (unsigned)L_s);
   if (d == 64)
-    score_lse_kernel<64, NCOL, MINB><<<grid, 256, 0, stream>>>(q, k_ctx, k_rec, neg_lse, H_q, G, (int)N, (int)N_q, chunk, c, inv_c);
+    score_lse_kernel<64, NCOL, 3><<<grid, 256, 0, stream>>>(q, k_ctx, k_rec, neg_lse, H_q, G, (int)N, (int)N_q, chunk, c, inv_c);
   else
-    score_lse_kernel<128, NCOL, MINB><<<grid, 256, 0, stream>>>(q, k_ctx, k_rec, neg_lse, H_q, G, (int)N, (int)N_q, chunk, c, inv_c);
+    score_lse_kernel<128, NCOL, 2><<<grid, 256, 0, stream>>>(q, k_ctx, k_rec, neg_lse, H_q, G, (int)N, (int)N_q, chunk, c, inv_c);
   return hipGetLastError();
 }
 
