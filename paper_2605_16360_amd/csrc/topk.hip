@@ -1,8 +1,9 @@
 // Per-row Top-K selection (paper Sec. 3: the mask keeps the Top-K of the mapped scores per target
 // layer and head; Sec. 4.3 names a Top-K kernel that materialises it).  Integer work only: scores
-// are turned into order-preserving 32-bit keys, the K-th largest key is found by a four-pass
-// 8-bit radix select, and one more ordered pass emits the kept indices in ascending order, taking
-// equal keys by lower index.
+// are turned into order-preserving 32-bit keys, the K-th largest key is found by an 8-bit radix select
+// (at most four passes) on the keys relative to the row's smallest key, and one more ordered pass emits the kept indices in ascending order, taking
+// equal keys by lower index.  A row of up to 36 864 scores is read from global memory once and its keys stay in
+// registers for all passes; longer rows are re-read (from L2) in every pass.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -20,7 +21,7 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// One workgroup per row.
+// One workgroup per row; the row is re-read (from L2) in every pass.  For rows longer than kTopkRegMax.
 __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restrict__ scores, int N, int K,
                                                             int32_t* __restrict__ idx_out) {
   const float* row = scores + (size_t)blockIdx.x * N;
@@ -30,15 +31,48 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
   __shared__ uint32_t s_prefix, s_krem;
   __shared__ uint32_t wave_gt[kTopkWaves], wave_eq[kTopkWaves];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  auto key_at = [&](int i) -> uint32_t { return order_key(row[i]); };
 
+  // Range of the row's keys: the radix digits are taken from key - kmin, top-aligned to the width of the
+  // range.  Digits of the raw key are badly skewed (scores share sign and exponent), and lanes that add to
+  // the same LDS counter are serialised; digits of the range-relative key are spread over all 256 bins.
+  __syncthreads();
+  uint32_t kmin = 0xffffffffu, kmax = 0u;
+  for (int i = tid; i < N; i += kTopkThreads) {
+    const uint32_t key = key_at(i);
+    kmin = key < kmin ? key : kmin;
+    kmax = key > kmax ? key : kmax;
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const uint32_t a = __shfl_xor(kmin, off, 64), c = __shfl_xor(kmax, off, 64);
+    kmin = a < kmin ? a : kmin;
+    kmax = c > kmax ? c : kmax;
+  }
+  if (lane == 0) {
+    wave_gt[wave] = kmin;
+    wave_eq[wave] = kmax;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kTopkWaves; ++w) {
+    kmin = wave_gt[w] < kmin ? wave_gt[w] : kmin;
+    kmax = wave_eq[w] > kmax ? wave_eq[w] : kmax;
+  }
+  const uint32_t span = kmax - kmin;
+  int prev_sh = span == 0 ? 0 : 32 - __builtin_clz(span);  // significant bits of key - kmin
+
+  // radix select on rel = key - kmin: `prefix` = the bits of the K-th largest rel above bit prev_sh
   uint32_t prefix = 0, krem = (uint32_t)K;
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
+  bool first = true;
+  while (prev_sh > 0) {
+    const int shift = prev_sh > 8 ? prev_sh - 8 : 0;
+    const uint32_t dmask = (1u << (prev_sh - shift)) - 1u;
     for (int i = tid; i < kTopkWaves * 256; i += kTopkThreads) (&hist[0][0])[i] = 0;
     __syncthreads();
     for (int i = tid; i < N; i += kTopkThreads) {
-      const uint32_t key = order_key(row[i]);
-      if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&hist[wave][(key >> shift) & 255u], 1u);
+      const uint32_t rel = key_at(i) - kmin;
+      if (first || (rel >> prev_sh) == prefix) atomicAdd(&hist[wave][(rel >> shift) & dmask], 1u);
     }
     __syncthreads();
     if (tid < 256) {
@@ -64,7 +98,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
 #pragma unroll
       for (int bsel = 0; bsel < 4; ++bsel) {
         if (above[bsel] < krem && krem <= above[bsel] + cnt[bsel]) {
-          s_prefix = (prefix << 8) | (uint32_t)(4 * lane + bsel);
+          s_prefix = (prefix << (prev_sh - shift)) | (uint32_t)(4 * lane + bsel);
           s_krem = krem - above[bsel];
         }
       }
@@ -72,7 +106,11 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
     __syncthreads();
     prefix = s_prefix;
     krem = s_krem;
+    prev_sh = shift;
+    first = false;
   }
+  prefix += kmin;  // back to a key; with all keys equal the loop did not run: T = kmin, K of them are taken
+  __syncthreads();
 
   // `prefix` is now the K-th largest key T; `krem` of the keys equal to T are kept, lowest index first.
   const uint32_t T = prefix, eq_take = krem;
@@ -80,7 +118,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
   for (int tile = 0; tile < N; tile += kTopkThreads) {
     const int i = tile + tid;
     const bool valid = i < N;
-    const uint32_t key = valid ? order_key(row[i]) : 0u;
+    const uint32_t key = valid ? key_at(i) : 0u;
     const bool gt = valid && key > T, eq = valid && key == T;
     const uint64_t bg = __builtin_amdgcn_ballot_w64(gt), be = __builtin_amdgcn_ballot_w64(eq);
     const uint64_t lower = (1ull << lane) - 1ull;
@@ -112,12 +150,174 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Rows of up to kTopkRegMax scores: thread t keeps the keys of the kTopkItems consecutive scores
+// [t * kTopkItems, (t + 1) * kTopkItems) in registers, so the row is read from memory once, every radix
+// pass runs on registers, and the ordered output needs one prefix sum over the threads' kept counts
+// instead of one per tile.
+// ---------------------------------------------------------------------------------------------
+constexpr int kTopkItems = 36;
+constexpr int kTopkRegMax = kTopkItems * kTopkThreads;
+
+// exclusive prefix sum of one value per thread over the workgroup (16 waves); also returns the total
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* wave_tot, int wave, int lane, uint32_t& total) {
+  uint32_t inc = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t t = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += t;
+  }
+  if (lane == 63) wave_tot[wave] = inc;
+  __syncthreads();
+  uint32_t before = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kTopkWaves; ++w) {
+    const uint32_t t = wave_tot[w];
+    if (w < wave) before += t;
+    tot += t;
+  }
+  __syncthreads();
+  total = tot;
+  return before + inc - v;
+}
+
+__global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float* __restrict__ scores, int N, int K,
+                                                                int32_t* __restrict__ idx_out) {
+  const float* row = scores + (size_t)blockIdx.x * N;
+  int32_t* out = idx_out + (size_t)blockIdx.x * K;
+  __shared__ uint32_t hist[kTopkWaves][256];
+  __shared__ uint32_t tot[256];
+  __shared__ uint32_t s_prefix, s_krem;
+  __shared__ uint32_t wave_a[kTopkWaves], wave_b[kTopkWaves];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int i0 = tid * kTopkItems;
+
+  // keys of this thread's scores; positions at and past N hold the key 0 and are never counted
+  uint32_t key[kTopkItems];
+  if ((reinterpret_cast<uintptr_t>(row) & 15) == 0 && i0 + kTopkItems <= N) {
+#pragma unroll
+    for (int j = 0; j < kTopkItems; j += 4) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(row + i0 + j);
+      key[j] = order_key(v[0]);
+      key[j + 1] = order_key(v[1]);
+      key[j + 2] = order_key(v[2]);
+      key[j + 3] = order_key(v[3]);
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < kTopkItems; ++j) key[j] = i0 + j < N ? order_key(row[i0 + j]) : 0u;
+  }
+  const int mine = N - i0 < 0 ? 0 : (N - i0 < kTopkItems ? N - i0 : kTopkItems);  // valid items of this thread
+
+  uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+  for (int j = 0; j < kTopkItems; ++j) {
+    if (j < mine) {
+      kmin = key[j] < kmin ? key[j] : kmin;
+      kmax = key[j] > kmax ? key[j] : kmax;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const uint32_t a = __shfl_xor(kmin, off, 64), c = __shfl_xor(kmax, off, 64);
+    kmin = a < kmin ? a : kmin;
+    kmax = c > kmax ? c : kmax;
+  }
+  if (lane == 0) {
+    wave_a[wave] = kmin;
+    wave_b[wave] = kmax;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kTopkWaves; ++w) {
+    kmin = wave_a[w] < kmin ? wave_a[w] : kmin;
+    kmax = wave_b[w] > kmax ? wave_b[w] : kmax;
+  }
+  const uint32_t span = kmax - kmin;
+  int prev_sh = span == 0 ? 0 : 32 - __builtin_clz(span);
+
+  uint32_t prefix = 0, krem = (uint32_t)K;
+  bool first = true;
+  while (prev_sh > 0) {
+    const int shift = prev_sh > 8 ? prev_sh - 8 : 0;
+    const uint32_t dmask = (1u << (prev_sh - shift)) - 1u;
+    for (int i = tid; i < kTopkWaves * 256; i += kTopkThreads) (&hist[0][0])[i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kTopkItems; ++j) {
+      const uint32_t rel = key[j] - kmin;
+      if (j < mine && (first || (rel >> prev_sh) == prefix)) atomicAdd(&hist[wave][(rel >> shift) & dmask], 1u);
+    }
+    __syncthreads();
+    if (tid < 256) {
+      uint32_t sum = 0;
+#pragma unroll
+      for (int w = 0; w < kTopkWaves; ++w) sum += hist[w][tid];
+      tot[tid] = sum;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      const uint32_t c0 = tot[4 * lane], c1 = tot[4 * lane + 1], c2 = tot[4 * lane + 2], c3 = tot[4 * lane + 3];
+      const uint32_t own = c0 + c1 + c2 + c3;
+      uint32_t v = own;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = __shfl_down(v, off, 64);
+        if (lane + off < 64) v += t;
+      }
+      const uint32_t a3 = v - own, a2 = a3 + c3, a1 = a2 + c2, a0 = a1 + c1;
+      const uint32_t above[4] = {a0, a1, a2, a3};
+      const uint32_t cnt[4] = {c0, c1, c2, c3};
+#pragma unroll
+      for (int bsel = 0; bsel < 4; ++bsel) {
+        if (above[bsel] < krem && krem <= above[bsel] + cnt[bsel]) {
+          s_prefix = (prefix << (prev_sh - shift)) | (uint32_t)(4 * lane + bsel);
+          s_krem = krem - above[bsel];
+        }
+      }
+    }
+    __syncthreads();
+    prefix = s_prefix;
+    krem = s_krem;
+    prev_sh = shift;
+    first = false;
+  }
+  const uint32_t T = prefix + kmin, eq_take = krem;
+
+  // kept: keys above T, and the eq_take lowest-index keys equal to T
+  uint32_t n_gt = 0, n_eq = 0;
+#pragma unroll
+  for (int j = 0; j < kTopkItems; ++j) {
+    if (j < mine) {
+      n_gt += key[j] > T;
+      n_eq += key[j] == T;
+    }
+  }
+  uint32_t tot_eq, tot_gt;
+  const uint32_t eq_before = block_exclusive_scan(n_eq, wave_a, wave, lane, tot_eq);
+  const uint32_t eq_mine = eq_before >= eq_take ? 0u : (eq_take - eq_before < n_eq ? eq_take - eq_before : n_eq);
+  uint32_t pos = block_exclusive_scan(n_gt + eq_mine, wave_b, wave, lane, tot_gt);
+  uint32_t eq_left = eq_mine;
+#pragma unroll
+  for (int j = 0; j < kTopkItems; ++j) {
+    if (j < mine) {
+      const bool take = key[j] > T || (key[j] == T && eq_left > 0);
+      if (key[j] == T && eq_left > 0) --eq_left;
+      if (take) out[pos++] = i0 + j;
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_topk(const float* scores, int64_t rows, int64_t N, int64_t K, int32_t* idx_out,
                        hipStream_t stream) {
   if (rows <= 0) return hipSuccess;
-  topk_kernel<<<dim3((unsigned)rows), kTopkThreads, 0, stream>>>(scores, (int)N, (int)K, idx_out);
+  if (N <= kTopkRegMax) {
+    topk_reg_kernel<<<dim3((unsigned)rows), kTopkThreads, 0, stream>>>(scores, (int)N, (int)K, idx_out);
+  } else {
+    topk_kernel<<<dim3((unsigned)rows), kTopkThreads, 0, stream>>>(scores, (int)N, (int)K, idx_out);
+  }
   return hipGetLastError();
 }
 
