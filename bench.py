@@ -95,6 +95,9 @@ def main():
     ap.add_argument("--case", default="llama_32k")
     ap.add_argument("--keep-ratio", type=float, default=0.3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--reduce", choices=("max", "sum"), default="max",
+                    help="reduction over the query axis: max (the headline path) or sum (the form Sec. 3 prints); "
+                         "with sum the stage reported as score_colmax is the column-sum kernel")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="after the timed steps, copy 1 GiB device to device with a plain torch copy kernel: the "
                          "known-size dispatch that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
@@ -121,7 +124,9 @@ def main():
     k_t, v_t = synth.make_target_kv(case, device=dev)
     note("target K/V generated")
     w = synth.make_mapper_weights(case.H_kv, case.H_l)
-    ctx = pk.proxykv_create(pk.config_for_case(case))
+    cfg = pk.config_for_case(case)
+    cfg.reduce = pk.PROXYKV_REDUCE_SUM if args.reduce == "sum" else pk.PROXYKV_REDUCE_MAX
+    ctx = pk.proxykv_create(cfg)
     pk.proxykv_set_mapper_weights(ctx, w)
     pk.proxykv_reserve(ctx, case.N, case.N_q)
     K = pk.proxykv_keep_count(case.N, args.keep_ratio)
@@ -170,7 +175,7 @@ def main():
         "value": case.N / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": case.name, "N": case.N, "N_q": case.N_q, "chunk": case.chunk, "keep_ratio": args.keep_ratio,
+        "config": {"workload": case.name, "reduce": args.reduce, "N": case.N, "N_q": case.N_q, "chunk": case.chunk, "keep_ratio": args.keep_ratio,
                    "K": K, "proxy": [case.L_s, case.H_q, case.H_kv, case.d], "target": [case.L_l, case.H_l, case.D]},
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": achieved, "peak": peak_tflops, "unit": "TFLOP/s",
                      "frac": achieved / peak_tflops, "traffic": measured_traffic(case.name, dominant)},

@@ -53,7 +53,8 @@ typedef enum { PROXYKV_BF16 = 0, PROXYKV_FP32 = 1 } proxykv_dtype;
 /* Reduction over the query axis that turns attention probabilities into a per-key score.
  * MAX: maximum over reconstruction queries and over the query heads of a GQA group (the
  * reconstruction-style score the proxy runs in place of the target's second prefill, Sec. 1/3).
- * SUM: the accumulation over the query axis printed in Sec. 3; not built (EUNSUPPORTED). */
+ * SUM: the accumulation over the query axis printed in Sec. 3, summed over the heads of the group as
+ * well; the same reconstruction queries, chunks and visibility as MAX. */
 typedef enum { PROXYKV_REDUCE_MAX = 0, PROXYKV_REDUCE_SUM = 1 } proxykv_reduce;
 
 typedef struct {
@@ -117,7 +118,8 @@ int proxykv_layer_pairing(const proxykv_config* cfg, int32_t* pairing_host);
  * Query i of query head h (KV head h / (H_q/H_kv)) sees the N context keys and the reconstruction
  * keys j of its own chunk (i / chunk == j / chunk) with j <= i; probabilities are the softmax of
  * <q, k> / sqrt(d) over that set; x_out[l, g, n] is the maximum probability that context key n
- * receives from any query of any head of group g.  QK^T runs on bf16 MFMA with fp32 accumulation. */
+ * receives from any query of any head of group g (reduce = MAX), or the sum of those probabilities
+ * over all of them (reduce = SUM).  QK^T runs on bf16 MFMA with fp32 accumulation. */
 int proxykv_score(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const void* k_rec,
                   int32_t dtype, int64_t N, int64_t N_q, int32_t chunk, float* x_out, void* stream);
 

@@ -36,7 +36,6 @@ int validate_config(const proxykv_config* c) {
   if (c->reduce != PROXYKV_REDUCE_MAX && c->reduce != PROXYKV_REDUCE_SUM) return PROXYKV_EINVAL;
   if (c->d != 64 && c->d != 128) return PROXYKV_EUNSUPPORTED;
   if ((c->D * 2) % 16 != 0) return PROXYKV_EUNSUPPORTED;
-  if (c->reduce != PROXYKV_REDUCE_MAX) return PROXYKV_EUNSUPPORTED;
   if (c->d_time != 512 || c->n_enc_heads != 8 || c->d_head_x != 64 || c->win != 2048 || c->stride != 1024 ||
       c->c_mid % 256 != 0 || c->d_ffn % 256 != 0 || c->H_kv > 16 || c->H_l > 64)
     return PROXYKV_EUNSUPPORTED;
@@ -207,7 +206,10 @@ int score_impl(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const voi
   if ((rcm = mark(ctx, 0, stream))) return rcm;
   PKV_HIP(ctx, pkv::launch_score_lse(q, kc, kr, nl, c.L_s, c.H_q, c.H_kv, c.d, N, N_q, chunk, stream));
   if ((rcm = mark(ctx, 1, stream))) return rcm;
-  PKV_HIP(ctx, pkv::launch_score_colmax(q, kc, nl, x_out, c.L_s, c.H_q, c.H_kv, c.d, N, N_q, stream));
+  if (c.reduce == PROXYKV_REDUCE_SUM)
+    PKV_HIP(ctx, pkv::launch_score_colsum(q, kc, nl, x_out, c.L_s, c.H_q, c.H_kv, c.d, N, N_q, stream));
+  else
+    PKV_HIP(ctx, pkv::launch_score_colmax(q, kc, nl, x_out, c.L_s, c.H_q, c.H_kv, c.d, N, N_q, stream));
   if ((rcm = mark(ctx, 2, stream))) return rcm;
   return PROXYKV_OK;
 }

@@ -171,6 +171,126 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void score_colmax_kernel(con
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// pass 2, sum form (the accumulation over the query axis that Sec. 3 prints for the proxy feature):
+//   x[l, hs, n] = sum over the heads g of the group and all queries i of 2^(c * (<q_i, k_n> + neg_lse[l, h, i]))
+// Same geometry as the max form (a workgroup owns 128*NCOL context keys as the resident B operand and
+// streams all G*N_q queries, -L2/c as the accumulator's initial value), but every element is exponentiated
+// and added: mul, exp2, add per element, so this kernel is bound by the vector ALU like pass 1.  A probability
+// never exceeds one, so there is no reference to track.  Rows past N_q carry -inf and add zero.
+// ---------------------------------------------------------------------------------------------
+template <int D, int NCOL>
+__global__ __launch_bounds__(256, 2) void score_colsum_kernel(const uint16_t* __restrict__ q,
+                                                               const uint16_t* __restrict__ k_ctx,
+                                                               const float* __restrict__ neg_lse,
+                                                               float* __restrict__ x, int H_q, int G, int N, int N_q,
+                                                               float c) {
+  using C = ScoreCfg<D>;
+  __shared__ u32x4 lds[kNBuf * C::TILE_U4];
+  __shared__ __attribute__((aligned(16))) float lds_nl[kNBuf * C::ROWS];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+  const int hs = blockIdx.y, l = blockIdx.z, H_kv = H_q / G;
+  constexpr int KB = 128 * NCOL;
+  const int n0 = blockIdx.x * KB;
+  const uint16_t* kc = k_ctx + (size_t)(l * H_kv + hs) * N * D;
+
+  bf16x8 b[NCOL][C::KK];
+  int kn[NCOL];
+  float colsum[NCOL];
+#pragma unroll
+  for (int cs = 0; cs < NCOL; ++cs) {
+    kn[cs] = n0 + (wave * NCOL + cs) * 32 + l32;
+    const int row = kn[cs] < N ? kn[cs] : N - 1;
+#pragma unroll
+    for (int kk = 0; kk < C::KK; ++kk)
+      b[cs][kk] = as_bf16x8(*reinterpret_cast<const u32x4*>(kc + (size_t)row * D + kk * 16 + half * 8));
+    colsum[cs] = 0.0f;
+  }
+
+  // tiles are fetched in order: head g = 0..G-1 of the group, query tile qt = 0..nqt-1
+  const int nqt = (N_q + C::ROWS - 1) / C::ROWS;
+  const int total = G * nqt;
+  TileRegs<D> regs;
+  float nl_reg = kNegInf;
+  int fg = 0, fqt = 0;
+  auto fetch_next = [&]() {
+    const size_t head = (size_t)(l * H_q + hs * G + fg);
+    tile_fetch<D>(regs, q + head * N_q * D, fqt * C::ROWS, N_q, tid);
+    if (tid < C::ROWS) {
+      const int i = fqt * C::ROWS + tid;
+      nl_reg = i < N_q ? neg_lse[head * N_q + i] : kNegInf;
+    }
+    if (++fqt == nqt) {
+      fqt = 0;
+      ++fg;
+    }
+  };
+  auto store = [&](int t) {
+    tile_store<D>(regs, lds + (t % kNBuf) * C::TILE_U4, tid);
+    if (tid < C::ROWS) lds_nl[(t % kNBuf) * C::ROWS + tid] = nl_reg;
+  };
+  fetch_next();
+  store(0);
+  if (total > 1) {
+    fetch_next();
+    store(1);
+  }
+  if (total > 2) fetch_next();
+
+  for (int t = 0; t < total; ++t) {
+    // every wave has finished tile t-1: its buffer takes tile t+2, the registers take tile t+3
+    __syncthreads();
+    if (t + 2 < total) store(t + 2);
+    if (t + 3 < total) fetch_next();
+    const u32x4* buf = lds + (t % kNBuf) * C::TILE_U4;
+    const float* nl = lds_nl + (t % kNBuf) * C::ROWS;
+#pragma unroll
+    for (int s = 0; s < C::SUB; ++s) {
+      bf16x8 a[C::KK];
+#pragma unroll
+      for (int kk = 0; kk < C::KK; ++kk) a[kk] = frag_read<D>(buf, s * 32 + l32, kk * 2 + half);
+      // accumulator rows of this lane: (r/4)*8 + half*4 + r%4
+      f32x16 init;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(&nl[s * 32 + j * 8 + half * 4]);
+        init[4 * j + 0] = v[0];
+        init[4 * j + 1] = v[1];
+        init[4 * j + 2] = v[2];
+        init[4 * j + 3] = v[3];
+      }
+#pragma unroll
+      for (int cp = 0; cp < NCOL; cp += 2) {
+        f32x16 acc[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          acc[e] = init;
+#pragma unroll
+          for (int kk = 0; kk < C::KK; ++kk) acc[e] = mfma_32x32x16(a[kk], b[cp + e][kk], acc[e]);
+        }
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          float s0 = __builtin_amdgcn_exp2f(acc[e][0] * c), s1 = __builtin_amdgcn_exp2f(acc[e][1] * c);
+          float s2 = __builtin_amdgcn_exp2f(acc[e][2] * c), s3 = __builtin_amdgcn_exp2f(acc[e][3] * c);
+#pragma unroll
+          for (int r = 4; r < 16; r += 4) {
+            s0 += __builtin_amdgcn_exp2f(acc[e][r + 0] * c);
+            s1 += __builtin_amdgcn_exp2f(acc[e][r + 1] * c);
+            s2 += __builtin_amdgcn_exp2f(acc[e][r + 2] * c);
+            s3 += __builtin_amdgcn_exp2f(acc[e][r + 3] * c);
+          }
+          colsum[cp + e] += (s0 + s1) + (s2 + s3);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int cs = 0; cs < NCOL; ++cs) {
+    const float tot = colsum[cs] + swap_halves(colsum[cs]);
+    if (half == 0 && kn[cs] < N) x[(size_t)(l * H_kv + hs) * N + kn[cs]] = tot;
+  }
+}
+
 __global__ void f32_to_bf16_kernel(const float* __restrict__ in, uint16_t* __restrict__ out, int64_t n) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) out[i] = f32_to_bf16_bits(in[i]);
@@ -182,6 +302,17 @@ hipError_t launch_f32_to_bf16(const float* in, uint16_t* out, int64_t n, hipStre
   if (n <= 0) return hipSuccess;
   const int blocks = (int)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
   f32_to_bf16_kernel<<<blocks, 256, 0, stream>>>(in, out, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_colsum(const uint16_t* q, const uint16_t* k_ctx, const float* neg_lse, float* x, int L_s,
+                               int H_q, int H_kv, int d, int64_t N, int64_t N_q, hipStream_t stream) {
+  const int G = H_q / H_kv;
+  const float c = 1.4426950408889634f / sqrtf((float)d);
+  constexpr int NCOL = 2;
+  dim3 grid((unsigned)((N + 128 * NCOL - 1) / (128 * NCOL)), (unsigned)H_kv, (unsigned)L_s);
+  if (d == 64) score_colsum_kernel<64, NCOL><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, (int)N, (int)N_q, c);
+  else score_colsum_kernel<128, NCOL><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, (int)N, (int)N_q, c);
   return hipGetLastError();
 }
 

@@ -53,7 +53,7 @@ def test_config_validation():
     pk.proxykv_destroy(ctx)
     for field, value, status in [("H_q", 30, pk.PROXYKV_EINVAL), ("L_s", 0, pk.PROXYKV_EINVAL),
                                  ("d", 96, pk.PROXYKV_EUNSUPPORTED), ("D", 100, pk.PROXYKV_EUNSUPPORTED),
-                                 ("reduce", pk.PROXYKV_REDUCE_SUM, pk.PROXYKV_EUNSUPPORTED), ("reduce", 7, pk.PROXYKV_EINVAL),
+                                 ("reduce", 7, pk.PROXYKV_EINVAL),
                                  ("d_time", 256, pk.PROXYKV_EUNSUPPORTED), ("stride", 4096, pk.PROXYKV_EINVAL)]:
         cfg = pk.make_config(16, 32, 8, 64, 32, 8, 128)
         setattr(cfg, field, value)

@@ -192,6 +192,27 @@ def test_llama_8k_full_size():
               map_samples=[(0, 0, 2048), (8, 3072, 4096), (15, N - 2048, N)])
 
 
+def test_llama_8k_sum_form_full_size():
+    """reduce = SUM at full size: one whole (layer, KV head) unit key by key; on other units the total over the
+    keys against the number of query rows (a row gives the context at most all of its probability, and at least
+    all but what its own chunk's prefix takes: bounded below through the first query of every chunk)."""
+    case = synth.CASES["llama_8k"]
+    cfg = pk.config_for_case(case)
+    cfg.reduce = pk.PROXYKV_REDUCE_SUM
+    ctx = pk.proxykv_create(cfg)
+    q, kc, kr = synth.make_proxy_qk(case, device="cuda")
+    x = pk.proxykv_score(ctx, q, kc, kr, case.chunk)
+    torch.cuda.synchronize()
+    G, (l, h) = case.G, (11, 6)
+    ref = oracle.score_unit(q[l, h * G:(h + 1) * G].double().cpu(), kc[l, h].double().cpu(), kr[l, h].double().cpu(),
+                            case.chunk, reduce="sum")
+    _close(x[l, h], ref, "score sum[llama_8k] unit (11, 6)")
+    tot = x.double().sum(dim=-1)
+    assert float(tot.max()) <= G * case.N_q * (1 + 1e-5) and float(tot.min()) > 0.5 * G * case.N_q
+    assert float(x.min()) >= 0.0
+    pk.proxykv_destroy(ctx)
+
+
 def test_llama_32k_full_size():
     """The workload bench.py times."""
     N = synth.CASES["llama_32k"].N

@@ -102,6 +102,22 @@ def test_score_matches_oracle(name):
     assert x_min >= 0.0 and x_max <= 1.0, (x_min, x_max)
 
 
+@pytest.mark.parametrize("name", list(SCORE_CASES))
+def test_score_sum_form_matches_oracle(name):
+    """reduce = SUM: the accumulation over the query axis that Sec. 3 prints, over all heads of the group."""
+    case = _score_case(name)
+    q, kc, kr = synth.make_proxy_qk(case)
+    ref = oracle.score(q.double(), kc.double(), kr.double(), case.chunk, reduce="sum")
+    cfg = pk.config_for_case(case)
+    cfg.reduce = pk.PROXYKV_REDUCE_SUM
+    ctx = pk.proxykv_create(cfg)
+    x = pk.proxykv_score(ctx, q.cuda(), kc.cuda(), kr.cuda(), case.chunk)
+    torch.cuda.synchronize()
+    assert_close(x, ref, f"score sum[{name}]")
+    # every query row spends at most all of its probability on the context keys
+    assert float(x.sum(dim=-1).max()) <= case.G * case.N_q * (1.0 + 1e-5)
+
+
 def test_score_tiny_case_fp32_inputs_and_planted_keys():
     case = synth.CASES["tiny"]
     q, kc, kr = synth.make_proxy_qk(case)
