@@ -95,6 +95,7 @@ def main():
     ap.add_argument("--case", default="llama_32k")
     ap.add_argument("--keep-ratio", type=float, default=0.3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", action="store_true", help="also time proxykv_compact_inplace and proxykv_mask once")
     ap.add_argument("--reduce", choices=("max", "sum"), default="max",
                     help="reduction over the query axis: max (the headline path) or sum (the form Sec. 3 prints); "
                          "with sum the stage reported as score_colmax is the column-sum kernel")
@@ -184,6 +185,20 @@ def main():
         "topk_compact_hbm": {"bytes": b_topk + b_comp, "achieved": hbm_gbps, "peak": 8000.0, "unit": "GB/s",
                              "frac": hbm_gbps / 8000.0},
     }
+    if args.extras:
+        # entry points outside the timed path: the cache compacted where it lies, and the byte mask
+        k_ip, v_ip = k_t.clone(), v_t.clone()
+        m = torch.empty(case.L_l, case.H_l, case.N, dtype=torch.uint8, device=dev)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        pk.proxykv_compact_inplace(ctx, k_ip, v_ip, idx, stream=stream)
+        ev[1].record()
+        pk.proxykv_mask(ctx, idx, case.N, mask_out=m, stream=stream)
+        ev[2].record()
+        torch.cuda.synchronize()
+        out["extras_ms"] = {"compact_inplace": ev[0].elapsed_time(ev[1]), "mask": ev[1].elapsed_time(ev[2])}
+        del k_ip, v_ip, m
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case, args.keep_ratio, x[0].float().cpu())
     print(json.dumps(out))

@@ -150,6 +150,20 @@ int proxykv_compact(proxykv_ctx* ctx, const void* k_in, const void* v_in, const 
                     int64_t rows, int64_t N, int64_t K, int64_t D, void* k_out, void* v_out,
                     void* stream);
 
+/* The same gather applied to the cache where it lies (Sec. 4.3: the mask is applied to the target's
+ * cache; App. B: the target's memory drops once it is): k, v [rows, N, D] 16-bit elements are both
+ * source and destination.  Afterwards tokens 0 .. K-1 of every row are the kept tokens in order
+ * (k[r, j, :] = old k[r, idx[r, j], :]); tokens K .. N-1 are left as they were.  idx [rows, K] must be
+ * strictly ascending within a row (as proxykv_topk writes it): the kernel relies on idx[r, j] >= j.
+ * D*2 bytes a multiple of 16 and at most 512. */
+int proxykv_compact_inplace(proxykv_ctx* ctx, void* k, void* v, const int32_t* idx, int64_t rows,
+                            int64_t N, int64_t K, int64_t D, void* stream);
+
+/* The binary mask M of Sec. 3 from the kept indices: mask_out [rows, N] uint8 (DEVICE),
+ * mask_out[r, n] = 1 if n is one of idx[r, 0 .. K-1], else 0.  Every byte of mask_out is written. */
+int proxykv_mask(proxykv_ctx* ctx, const int32_t* idx, int64_t rows, int64_t N, int64_t K,
+                 uint8_t* mask_out, void* stream);
+
 /* The whole path on one stream: score -> map -> top-k -> compact, with
  * K = proxykv_keep_count(N, keep_ratio) written to *K_host (HOST, may be NULL).
  *   k_in, v_in [L_l, H_l, N, D]; k_out, v_out [L_l, H_l, K, D]; idx_out [L_l, H_l, K] int32;

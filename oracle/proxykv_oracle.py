@@ -417,6 +417,14 @@ def topk(scores: torch.Tensor, K: int) -> torch.Tensor:
     return out
 
 
+def mask(idx: torch.Tensor, N: int) -> torch.Tensor:
+    """The binary mask M of Sec. 3 (M in {0,1}^{B x L_l x H_l x N}) from the kept
+    indices idx [..., K]: M[..., n] = 1 exactly for the kept tokens.  uint8."""
+    M = torch.zeros(*idx.shape[:-1], N, dtype=torch.uint8)
+    M.scatter_(-1, idx.to(torch.int64), torch.ones(idx.shape, dtype=torch.uint8))
+    return M
+
+
 def compact(kv: torch.Tensor, idx: torch.Tensor) -> torch.Tensor:
     """Apply the mask to a KV tensor (Sec. 3 and Sec. 4.3): kv [..., N, D] and
     idx [..., K] -> out [..., K, D] with out[..., j, :] = kv[..., idx[..., j], :].

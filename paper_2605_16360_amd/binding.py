@@ -20,7 +20,8 @@ PROXYKV_REDUCE_MAX, PROXYKV_REDUCE_SUM = 0, 1
 EXPORTS = [
     "proxykv_default_mapper", "proxykv_create", "proxykv_destroy", "proxykv_mapper_weight_count",
     "proxykv_set_mapper_weights", "proxykv_workspace_bytes", "proxykv_reserve", "proxykv_keep_count",
-    "proxykv_layer_pairing", "proxykv_score", "proxykv_map", "proxykv_topk", "proxykv_compact", "proxykv_prune",
+    "proxykv_layer_pairing", "proxykv_score", "proxykv_map", "proxykv_topk", "proxykv_compact", "proxykv_compact_inplace",
+    "proxykv_mask", "proxykv_prune",
     "proxykv_profile_enable", "proxykv_profile_read", "proxykv_strerror", "proxykv_last_hip_error",
 ]
 STAGES = ("score_lse", "score_colmax", "map", "topk", "compact")
@@ -68,6 +69,8 @@ def load() -> ctypes.CDLL:
     lib.proxykv_map.argtypes = [vp, vp, i64, vp, vp]
     lib.proxykv_topk.argtypes = [vp, vp, i64, i64, i64, vp, vp]
     lib.proxykv_compact.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp, vp]
+    lib.proxykv_compact_inplace.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp]
+    lib.proxykv_mask.argtypes = [vp, vp, i64, i64, i64, vp, vp]
     lib.proxykv_prune.argtypes = [vp, vp, vp, vp, i32, i64, i64, i32, f64, vp, vp, vp, vp, vp, vp, vp,
                                   ctypes.POINTER(i64), vp]
     lib.proxykv_profile_enable.argtypes = [vp, ctypes.c_int]
@@ -269,6 +272,26 @@ def proxykv_compact(ctx: Context, k_in, v_in, idx, k_out=None, v_out=None, strea
                                   _dev_ptr(idx, "idx", torch.int32), rows, N, K, D, _dev_ptr(k_out, "k_out"),
                                   _dev_ptr(v_out, "v_out"), _stream_ptr(stream)), "proxykv_compact", ctx.handle)
     return k_out, v_out
+
+
+def proxykv_compact_inplace(ctx: Context, k, v, idx, stream=None) -> None:
+    """k, v [..., N, D] are compacted where they lie: tokens 0 .. K-1 of every row become the kept tokens."""
+    N, D = k.shape[-2], k.shape[-1]
+    K = idx.shape[-1]
+    rows = idx.numel() // K
+    assert k.shape == v.shape and k.numel() == rows * N * D and k.element_size() == 2
+    _check(load().proxykv_compact_inplace(ctx.handle, _dev_ptr(k, "k"), _dev_ptr(v, "v"), _dev_ptr(idx, "idx", torch.int32),
+                                          rows, N, K, D, _stream_ptr(stream)), "proxykv_compact_inplace", ctx.handle)
+
+
+def proxykv_mask(ctx: Context, idx, N: int, mask_out=None, stream=None) -> torch.Tensor:
+    K = idx.shape[-1]
+    rows = idx.numel() // K
+    if mask_out is None:
+        mask_out = torch.empty(*idx.shape[:-1], N, dtype=torch.uint8, device=idx.device)
+    _check(load().proxykv_mask(ctx.handle, _dev_ptr(idx, "idx", torch.int32), rows, N, K, _dev_ptr(mask_out, "mask_out", torch.uint8),
+                               _stream_ptr(stream)), "proxykv_mask", ctx.handle)
+    return mask_out
 
 
 def proxykv_prune(ctx: Context, q_rec, k_ctx, k_rec, chunk: int, keep_ratio: float, k_in, v_in, k_out=None, v_out=None,

@@ -470,6 +470,24 @@ int proxykv_compact(proxykv_ctx* ctx, const void* k_in, const void* v_in, const 
   return PROXYKV_OK;
 }
 
+int proxykv_compact_inplace(proxykv_ctx* ctx, void* k, void* v, const int32_t* idx, int64_t rows, int64_t N, int64_t K,
+                            int64_t D, void* stream) {
+  if (!ctx || !k || !v || !idx) return PROXYKV_EINVAL;
+  if (rows <= 0 || N <= 0 || N >= (1ll << 31) || K < 1 || K > N || D <= 0) return PROXYKV_EINVAL;
+  if ((D * 2) % 16 != 0 || D * 2 > 512) return PROXYKV_EUNSUPPORTED;
+  PKV_HIP(ctx, hipSetDevice(ctx->cfg.device));
+  PKV_HIP(ctx, pkv::launch_compact_inplace(k, v, idx, rows, N, K, D * 2, (hipStream_t)stream));
+  return PROXYKV_OK;
+}
+
+int proxykv_mask(proxykv_ctx* ctx, const int32_t* idx, int64_t rows, int64_t N, int64_t K, uint8_t* mask_out, void* stream) {
+  if (!ctx || !idx || !mask_out) return PROXYKV_EINVAL;
+  if (rows <= 0 || N <= 0 || N >= (1ll << 31) || K < 1 || K > N) return PROXYKV_EINVAL;
+  PKV_HIP(ctx, hipSetDevice(ctx->cfg.device));
+  PKV_HIP(ctx, pkv::launch_mask(idx, rows, N, K, mask_out, (hipStream_t)stream));
+  return PROXYKV_OK;
+}
+
 int proxykv_prune(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const void* k_rec, int32_t dtype, int64_t N,
                   int64_t N_q, int32_t chunk, double keep_ratio, const void* k_in, const void* v_in, void* k_out,
                   void* v_out, int32_t* idx_out, float* x_out, float* yhat_out, int64_t* K_host, void* stream) {

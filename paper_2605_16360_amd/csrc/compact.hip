@@ -40,6 +40,83 @@ __global__ __launch_bounds__(256) void compact_kernel(const u32x4* __restrict__ 
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same gather with the cache as its own destination (the paper's mask is applied to the target's
+// cache where it lies): afterwards tokens 0 .. K-1 of every row r are the kept tokens in order; what
+// lies behind them is not touched.  idx is ascending, so token j moves from idx[j] >= j: a destination
+// never lies behind its source, and the only hazard is a later token's destination overwriting an
+// earlier token's source before it was read.  One workgroup per row walks the kept tokens in chunks
+// of 128 in order: the loads of chunk c+1 are issued, a barrier makes sure every thread holds chunk
+// c, then chunk c is stored.  Chunk c+1 reads tokens at or behind (c+1)*128, which chunk c's stores
+// (tokens below (c+1)*128) cannot touch, so the two overlap safely.
+// grid (rows), 256 threads; cpr = 16-byte chunks per token (<= 32).
+// ---------------------------------------------------------------------------------------------
+constexpr int kInplaceTokens = 128;
+
+template <int PER>  // 16-byte pieces per thread and chunk, for each of K and V
+__global__ __launch_bounds__(256) void compact_inplace_kernel(u32x4* __restrict__ k, u32x4* __restrict__ v,
+                                                               const int32_t* __restrict__ idx, int64_t N, int K, int cpr) {
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const int32_t* ridx = idx + (size_t)r * K;
+  u32x4* kb = k + (size_t)r * N * cpr;
+  u32x4* vb = v + (size_t)r * N * cpr;
+  const int n_chunks = (K + kInplaceTokens - 1) / kInplaceTokens;
+  u32x4 ka[PER], va[PER], kn[PER], vn[PER];
+  auto load = [&](int c, u32x4 (&kr)[PER], u32x4 (&vr)[PER]) {
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int piece = tid + 256 * u, j = c * kInplaceTokens + piece / cpr, ch = piece % cpr;
+      if (piece < kInplaceTokens * cpr && j < K) {
+        const size_t src = (size_t)ridx[j] * cpr + ch;
+        kr[u] = __builtin_nontemporal_load(kb + src);
+        vr[u] = __builtin_nontemporal_load(vb + src);
+      }
+    }
+  };
+  auto store = [&](int c, const u32x4 (&kr)[PER], const u32x4 (&vr)[PER]) {
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int piece = tid + 256 * u, j = c * kInplaceTokens + piece / cpr, ch = piece % cpr;
+      if (piece < kInplaceTokens * cpr && j < K) {
+        const size_t dst = (size_t)j * cpr + ch;
+        kb[dst] = kr[u];
+        vb[dst] = vr[u];
+      }
+    }
+  };
+  load(0, ka, va);
+  for (int c = 0; c < n_chunks; ++c) {
+    if (c + 1 < n_chunks) load(c + 1, kn, vn);
+    // every thread holds its part of chunk c (and of every chunk before it) before any of chunk c is stored
+    __syncthreads();
+    store(c, ka, va);
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      ka[u] = kn[u];
+      va[u] = vn[u];
+    }
+  }
+}
+
+// mask[r, n] = 1 for the kept tokens of row r, 0 elsewhere (uint8).  One workgroup per row clears the row,
+// then sets the kept positions.
+__global__ __launch_bounds__(256) void mask_kernel(const int32_t* __restrict__ idx, int64_t N, int K,
+                                                    uint8_t* __restrict__ mask) {
+  const int r = blockIdx.x, tid = threadIdx.x;
+  uint8_t* row = mask + (size_t)r * N;
+  // 16-byte stores over the aligned middle, bytes at the ragged ends
+  const uintptr_t addr = reinterpret_cast<uintptr_t>(row);
+  const int64_t head = (int64_t)((16 - (addr & 15)) & 15) < N ? (int64_t)((16 - (addr & 15)) & 15) : N;
+  const int64_t n16 = (N - head) / 16;
+  for (int64_t i = tid; i < head; i += 256) row[i] = 0;
+  u32x4* mid = reinterpret_cast<u32x4*>(row + head);
+  for (int64_t i = tid; i < n16; i += 256) mid[i] = u32x4{0, 0, 0, 0};
+  for (int64_t i = head + n16 * 16 + tid; i < N; i += 256) row[i] = 0;
+  __syncthreads();  // workgroup-scope release/acquire: the zeros are in place before the ones
+  const int32_t* ridx = idx + (size_t)r * K;
+  for (int j = tid; j < K; j += 256) row[ridx[j]] = 1;
+}
+
 }  // namespace
 
 hipError_t launch_compact(const void* k_in, const void* v_in, const int32_t* idx, int64_t rows, int64_t N, int64_t K,
@@ -50,6 +127,25 @@ hipError_t launch_compact(const void* k_in, const void* v_in, const int32_t* idx
   dim3 grid((unsigned)((K + tokens_per_block - 1) / tokens_per_block), (unsigned)rows);
   compact_kernel<<<grid, 256, 0, stream>>>((const u32x4*)k_in, (const u32x4*)v_in, idx, N, (int)K, cpr,
                                            (u32x4*)k_out, (u32x4*)v_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact_inplace(void* k, void* v, const int32_t* idx, int64_t rows, int64_t N, int64_t K, int64_t row_bytes,
+                                  hipStream_t stream) {
+  if (rows <= 0 || K <= 0) return hipSuccess;
+  const int cpr = (int)(row_bytes / 16);
+  const int per = (kInplaceTokens * cpr + 255) / 256;  // 16-byte pieces per thread and chunk
+  u32x4 *kp = (u32x4*)k, *vp = (u32x4*)v;
+  if (per <= 4) compact_inplace_kernel<4><<<(unsigned)rows, 256, 0, stream>>>(kp, vp, idx, N, (int)K, cpr);
+  else if (per <= 8) compact_inplace_kernel<8><<<(unsigned)rows, 256, 0, stream>>>(kp, vp, idx, N, (int)K, cpr);
+  else if (per <= 16) compact_inplace_kernel<16><<<(unsigned)rows, 256, 0, stream>>>(kp, vp, idx, N, (int)K, cpr);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_mask(const int32_t* idx, int64_t rows, int64_t N, int64_t K, uint8_t* mask, hipStream_t stream) {
+  if (rows <= 0) return hipSuccess;
+  mask_kernel<<<(unsigned)rows, 256, 0, stream>>>(idx, N, (int)K, mask);
   return hipGetLastError();
 }
 

@@ -28,4 +28,9 @@ hipError_t launch_topk(const float* scores, int64_t rows, int64_t N, int64_t K, 
 hipError_t launch_compact(const void* k_in, const void* v_in, const int32_t* idx, int64_t rows, int64_t N,
                           int64_t K, int64_t row_bytes, void* k_out, void* v_out, hipStream_t stream);
 
+// In-place variant: tokens 0 .. K-1 of every row of k and v become the kept tokens in order.
+hipError_t launch_compact_inplace(void* k, void* v, const int32_t* idx, int64_t rows, int64_t N, int64_t K, int64_t row_bytes,
+                                  hipStream_t stream);
+// mask[r, n] = 1 if n is one of idx[r, :], else 0.
+hipError_t launch_mask(const int32_t* idx, int64_t rows, int64_t N, int64_t K, uint8_t* mask, hipStream_t stream);
 }  // namespace pkv

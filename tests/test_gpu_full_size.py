@@ -11,7 +11,8 @@ Every oracle input comes from the seeded generator (synth), never from the HIP p
                the singly covered ends and the ragged tail) for every target layer paired with the sampled
                proxy layer;
   * top-k    - proxykv_topk on a seeded array of the full shape, every row, bit-exact;
-  * compact  - proxykv_compact on the full target cache, sampled (layer, head) rows, bit-exact.
+  * compact  - proxykv_compact and proxykv_compact_inplace on the full target cache, sampled (layer, head)
+               rows, bit-exact; proxykv_mask, every row.
 The fused call is then tied to the stage calls: on the same inputs it returns the same bits as
 score -> map -> top-k -> compact called one by one.
 Floating point: |gpu - ref| <= 2e-3 + 1e-2 |ref|.
@@ -147,10 +148,19 @@ def _check_topk_compact(case, ctx, keep_ratio, rows_sampled=6):
     rng = np.random.default_rng(11)
     picks = {(0, 0), (case.L_l - 1, case.H_l - 1)} | {(int(rng.integers(case.L_l)), int(rng.integers(case.H_l)))
                                                        for _ in range(rows_sampled - 2)}
+    # the same gather with the cache as its own destination, and the byte mask
+    k_ip, v_ip = k_t.clone(), v_t.clone()
+    pk.proxykv_compact_inplace(ctx, k_ip, v_ip, idx_l)
+    m = pk.proxykv_mask(ctx, idx_l, N)
+    torch.cuda.synchronize()
+    assert torch.equal(m.cpu(), oracle.mask(ref.view(case.L_l, case.H_l, K), N)), f"mask[{case.name}] differs"
     for (l, h) in sorted(picks):
-        for src, out in ((k_t, k_out), (v_t, v_out)):
+        for src, out, inplace in ((k_t, k_out, k_ip), (v_t, v_out, v_ip)):
             exp = oracle.compact(src[l:l + 1, h:h + 1].cpu(), idx_l[l:l + 1, h:h + 1].cpu())
             assert torch.equal(out[l:l + 1, h:h + 1].cpu().view(torch.int16), exp.view(torch.int16)), (case.name, l, h)
+            assert torch.equal(inplace[l:l + 1, h:h + 1, :K].cpu().view(torch.int16), exp.view(torch.int16)), (case.name, l, h)
+            assert torch.equal(inplace[l, h, K:].view(torch.int16), src[l, h, K:].view(torch.int16)), (case.name, l, h)
+    del k_ip, v_ip
     return k_t, v_t
 
 

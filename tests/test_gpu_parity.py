@@ -71,6 +71,27 @@ def test_compact_bit_exact():
         assert torch.equal(v_out.cpu().view(torch.int16), oracle.compact(kv[1], idx).view(torch.int16))
 
 
+def test_compact_inplace_and_mask_bit_exact():
+    """The cache as its own destination: tokens 0 .. K-1 equal the out-of-place gather, the rest is untouched;
+    the byte mask marks exactly the kept tokens.  Dense kept sets (sources right behind destinations), K = N,
+    K = 1, several chunks of 128 with a ragged last one, unaligned mask rows."""
+    ctx = _ctx(synth.CASES["tiny"])
+    g = torch.Generator().manual_seed(4)
+    for (L, H, N, D, K) in [(2, 3, 700, 128, 211), (1, 2, 130, 64, 130), (1, 1, 9, 128, 1), (1, 2, 1000, 128, 999),
+                            (2, 2, 1537, 128, 640), (1, 3, 333, 256, 129)]:
+        kv = torch.randn(2, L, H, N, D, generator=g).to(torch.bfloat16)
+        s = torch.randn(L * H, N, generator=g)
+        idx = oracle.topk(s, K).view(L, H, K)
+        k, v = kv[0].cuda(), kv[1].cuda()
+        pk.proxykv_compact_inplace(ctx, k, v, idx.cuda())
+        m = pk.proxykv_mask(ctx, idx.cuda(), N)
+        torch.cuda.synchronize()
+        for got, src in ((k, kv[0]), (v, kv[1])):
+            assert torch.equal(got[..., :K, :].cpu().view(torch.int16), oracle.compact(src, idx).view(torch.int16)), (N, K)
+            assert torch.equal(got[..., K:, :].cpu().view(torch.int16), src[..., K:, :].view(torch.int16)), (N, K)
+        assert torch.equal(m.cpu(), oracle.mask(idx, N)), (N, K)
+
+
 # ----------------------------------------------------------------------------------------------
 # scoring
 # ----------------------------------------------------------------------------------------------

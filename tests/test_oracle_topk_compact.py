@@ -85,3 +85,19 @@ def test_compact_is_an_ordered_gather():
     marker = torch.arange(40, dtype=torch.float32).view(1, 1, 40, 1).expand(2, 3, 40, 8).contiguous()
     got = oracle.compact(marker, idx)[..., 0]
     assert bool((got[..., 1:] > got[..., :-1]).all())
+
+
+def test_mask_marks_exactly_the_kept_tokens():
+    g = torch.Generator().manual_seed(12)
+    s = torch.randn(6, 50, generator=g)
+    idx = oracle.topk(s, 17).view(2, 3, 17)
+    M = oracle.mask(idx, 50)
+    assert M.shape == (2, 3, 50) and M.dtype == torch.uint8
+    for l in range(2):
+        for h in range(3):
+            kept = set(idx[l, h].tolist())
+            assert [int(v) for v in M[l, h]] == [1 if n in kept else 0 for n in range(50)]
+    assert int(M.sum()) == 6 * 17
+    # the mask selects the same rows, in the same order, as the gather
+    kv = torch.randn(2, 3, 50, 4, generator=g)
+    assert torch.equal(kv[M.bool()].view(2, 3, 17, 4), oracle.compact(kv, idx))
