@@ -232,16 +232,27 @@ def main():
         # entry points outside the timed path: the cache compacted where it lies, and the byte mask
         k_ip, v_ip = k_t.clone(), v_t.clone()
         m = torch.empty(case.L_l, case.H_l, case.N, dtype=torch.uint8, device=dev)
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        # and the selection with one budget per layer shared by its heads, on the mapper's output for x
+        y = pk.proxykv_map(ctx, x)
+        flat = torch.empty(case.L_l, case.H_l * K, dtype=torch.int32, device=dev)
+        counts = torch.empty(case.L_l, case.H_l, dtype=torch.int32, device=dev)
+        k_pl, v_pl = k_t.clone(), v_t.clone()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
         torch.cuda.synchronize()
         ev[0].record()
         pk.proxykv_compact_inplace(ctx, k_ip, v_ip, idx, stream=stream)
         ev[1].record()
         pk.proxykv_mask(ctx, idx, case.N, mask_out=m, stream=stream)
         ev[2].record()
+        pk.proxykv_topk_pooled(ctx, y, K, flat_out=flat, counts_out=counts, stream=stream)
+        ev[3].record()
+        pk.proxykv_compact_pooled(ctx, k_pl, v_pl, flat, counts, stream=stream)
+        ev[4].record()
         torch.cuda.synchronize()
-        out["extras_ms"] = {"compact_inplace": ev[0].elapsed_time(ev[1]), "mask": ev[1].elapsed_time(ev[2])}
-        del k_ip, v_ip, m
+        out["extras_ms"] = {"compact_inplace": ev[0].elapsed_time(ev[1]), "mask": ev[1].elapsed_time(ev[2]),
+                            "topk_pooled": ev[2].elapsed_time(ev[3]), "compact_pooled": ev[3].elapsed_time(ev[4]),
+                            "pooled_counts_min_max": [int(counts.min()), int(counts.max())]}
+        del k_ip, v_ip, m, k_pl, v_pl, y
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case, args.keep_ratio, x[0].float().cpu())
     print(json.dumps(out))

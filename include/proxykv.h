@@ -164,6 +164,25 @@ int proxykv_compact_inplace(proxykv_ctx* ctx, void* k, void* v, const int32_t* i
 int proxykv_mask(proxykv_ctx* ctx, const int32_t* idx, int64_t rows, int64_t N, int64_t K,
                  uint8_t* mask_out, void* stream);
 
+/* Top-K with one budget per target layer instead of one per head (Sec. 3 thresholds the mapped scores
+ * at a retention ratio and does not say whether heads share it; KVZip, whose scores the mapper
+ * imitates, lets them): scores [layers, heads, N] fp32; of a layer's heads*N (head, token) pairs the
+ * heads*K that come first under proxykv_topk's order (ties to the lower flat index h*N + n) are kept.
+ *   flat_out [layers, heads*K] int32: the kept flat indices h*N + n, ascending, so the tokens of
+ *     head h are the entries in [h*N, (h+1)*N) minus h*N, ascending, and follow those of head h-1;
+ *   counts_out [layers, heads] int32: how many of them belong to each head (sum = heads*K).
+ * heads*N must stay below 2^31 - 4096. */
+int proxykv_topk_pooled(proxykv_ctx* ctx, const float* scores, int64_t layers, int64_t heads,
+                        int64_t N, int64_t K, int32_t* flat_out, int32_t* counts_out, void* stream);
+
+/* proxykv_compact_inplace for the lists proxykv_topk_pooled writes: k, v [layers, heads, N, D] 16-bit
+ * elements; afterwards tokens 0 .. counts[l, h]-1 of row (l, h) are that head's kept tokens in order,
+ * the rest of the row is left as it was.  flat and counts must be a pair written by
+ * proxykv_topk_pooled with the same layers, heads, N, K (not checked on the device). */
+int proxykv_compact_pooled(proxykv_ctx* ctx, void* k, void* v, const int32_t* flat,
+                           const int32_t* counts, int64_t layers, int64_t heads, int64_t N, int64_t K,
+                           int64_t D, void* stream);
+
 /* The whole path on one stream: score -> map -> top-k -> compact, with
  * K = proxykv_keep_count(N, keep_ratio) written to *K_host (HOST, may be NULL).
  *   k_in, v_in [L_l, H_l, N, D]; k_out, v_out [L_l, H_l, K, D]; idx_out [L_l, H_l, K] int32;

@@ -23,6 +23,7 @@ from .proxykv_oracle import (  # noqa: F401
     mapper_layer,
     mapper,
     topk,
+    topk_pooled,
     mask,
     compact,
     prune,

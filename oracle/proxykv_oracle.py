@@ -417,6 +417,24 @@ def topk(scores: torch.Tensor, K: int) -> torch.Tensor:
     return out
 
 
+def topk_pooled(scores: torch.Tensor, K_per_head: int) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Non-uniform head budgets: one selection per target layer over the pooled
+    scores of all its heads (the paper thresholds Y_hat at a retention ratio,
+    Sec. 3, and leaves open whether the budget is per head or shared; KVZip,
+    whose score the proxy imitates, shares it across heads).  scores [L, H, N];
+    the H*K_per_head best (head, token) pairs of a layer are kept under the total
+    order of `topk` applied to the row of length H*N (higher score first, ties to
+    the lower flat index h*N + n).  Returns (flat [L, H*K_per_head] int32, the kept
+    flat indices ascending, so head h's tokens are the entries in [h*N, (h+1)*N)
+    minus h*N, ascending; counts [L, H] int32, the number kept per head)."""
+    L, H, N = scores.shape
+    flat = topk(scores.reshape(L, H * N), H * K_per_head)
+    counts = torch.zeros(L, H, dtype=torch.int32)
+    for l in range(L):
+        counts[l] = torch.bincount(torch.div(flat[l].to(torch.int64), N, rounding_mode="floor"), minlength=H).to(torch.int32)
+    return flat, counts
+
+
 def mask(idx: torch.Tensor, N: int) -> torch.Tensor:
     """The binary mask M of Sec. 3 (M in {0,1}^{B x L_l x H_l x N}) from the kept
     indices idx [..., K]: M[..., n] = 1 exactly for the kept tokens.  uint8."""

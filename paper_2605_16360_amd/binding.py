@@ -21,7 +21,7 @@ EXPORTS = [
     "proxykv_default_mapper", "proxykv_create", "proxykv_destroy", "proxykv_mapper_weight_count",
     "proxykv_set_mapper_weights", "proxykv_workspace_bytes", "proxykv_reserve", "proxykv_keep_count",
     "proxykv_layer_pairing", "proxykv_score", "proxykv_map", "proxykv_topk", "proxykv_compact", "proxykv_compact_inplace",
-    "proxykv_mask", "proxykv_prune",
+    "proxykv_mask", "proxykv_topk_pooled", "proxykv_compact_pooled", "proxykv_prune",
     "proxykv_profile_enable", "proxykv_profile_read", "proxykv_strerror", "proxykv_last_hip_error",
 ]
 STAGES = ("score_lse", "score_colmax", "map", "topk", "compact")
@@ -71,6 +71,8 @@ def load() -> ctypes.CDLL:
     lib.proxykv_compact.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp, vp]
     lib.proxykv_compact_inplace.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp]
     lib.proxykv_mask.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+    lib.proxykv_topk_pooled.argtypes = [vp, vp, i64, i64, i64, i64, vp, vp, vp]
+    lib.proxykv_compact_pooled.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
     lib.proxykv_prune.argtypes = [vp, vp, vp, vp, i32, i64, i64, i32, f64, vp, vp, vp, vp, vp, vp, vp,
                                   ctypes.POINTER(i64), vp]
     lib.proxykv_profile_enable.argtypes = [vp, ctypes.c_int]
@@ -292,6 +294,29 @@ def proxykv_mask(ctx: Context, idx, N: int, mask_out=None, stream=None) -> torch
     _check(load().proxykv_mask(ctx.handle, _dev_ptr(idx, "idx", torch.int32), rows, N, K, _dev_ptr(mask_out, "mask_out", torch.uint8),
                                _stream_ptr(stream)), "proxykv_mask", ctx.handle)
     return mask_out
+
+
+def proxykv_topk_pooled(ctx: Context, scores, K: int, flat_out=None, counts_out=None, stream=None):
+    """scores [layers, heads, N]; one budget of heads*K per layer.  Returns (flat [layers, heads*K], counts [layers, heads])."""
+    layers, heads, N = scores.shape
+    if flat_out is None:
+        flat_out = torch.empty(layers, heads * K, dtype=torch.int32, device=scores.device)
+    if counts_out is None:
+        counts_out = torch.empty(layers, heads, dtype=torch.int32, device=scores.device)
+    _check(load().proxykv_topk_pooled(ctx.handle, _dev_ptr(scores, "scores", torch.float32), layers, heads, N, K,
+                                      _dev_ptr(flat_out, "flat_out", torch.int32), _dev_ptr(counts_out, "counts_out", torch.int32),
+                                      _stream_ptr(stream)), "proxykv_topk_pooled", ctx.handle)
+    return flat_out, counts_out
+
+
+def proxykv_compact_pooled(ctx: Context, k, v, flat, counts, stream=None) -> None:
+    """k, v [layers, heads, N, D] compacted where they lie with the ragged lists of proxykv_topk_pooled."""
+    layers, heads, N, D = k.shape
+    K = flat.shape[-1] // heads
+    assert k.shape == v.shape and k.element_size() == 2 and flat.shape == (layers, heads * K) and counts.shape == (layers, heads)
+    _check(load().proxykv_compact_pooled(ctx.handle, _dev_ptr(k, "k"), _dev_ptr(v, "v"), _dev_ptr(flat, "flat", torch.int32),
+                                         _dev_ptr(counts, "counts", torch.int32), layers, heads, N, K, D, _stream_ptr(stream)),
+           "proxykv_compact_pooled", ctx.handle)
 
 
 def proxykv_prune(ctx: Context, q_rec, k_ctx, k_rec, chunk: int, keep_ratio: float, k_in, v_in, k_out=None, v_out=None,

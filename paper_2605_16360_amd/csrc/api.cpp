@@ -476,7 +476,29 @@ int proxykv_compact_inplace(proxykv_ctx* ctx, void* k, void* v, const int32_t* i
   if (rows <= 0 || N <= 0 || N >= (1ll << 31) || K < 1 || K > N || D <= 0) return PROXYKV_EINVAL;
   if ((D * 2) % 16 != 0 || D * 2 > 512) return PROXYKV_EUNSUPPORTED;
   PKV_HIP(ctx, hipSetDevice(ctx->cfg.device));
-  PKV_HIP(ctx, pkv::launch_compact_inplace(k, v, idx, rows, N, K, D * 2, (hipStream_t)stream));
+  PKV_HIP(ctx, pkv::launch_compact_inplace(k, v, idx, rows, N, K, D * 2, nullptr, 1, (hipStream_t)stream));
+  return PROXYKV_OK;
+}
+
+int proxykv_topk_pooled(proxykv_ctx* ctx, const float* scores, int64_t layers, int64_t heads, int64_t N, int64_t K,
+                        int32_t* flat_out, int32_t* counts_out, void* stream) {
+  if (!ctx || !scores || !flat_out || !counts_out) return PROXYKV_EINVAL;
+  if (layers <= 0 || heads <= 0 || N <= 0 || K < 1 || K > N) return PROXYKV_EINVAL;
+  if (layers * heads >= (1ll << 31) || heads * N >= (1ll << 31) - 4096) return PROXYKV_EINVAL;
+  PKV_HIP(ctx, hipSetDevice(ctx->cfg.device));
+  PKV_HIP(ctx, pkv::launch_topk(scores, layers, heads * N, heads * K, flat_out, (hipStream_t)stream));
+  PKV_HIP(ctx, pkv::launch_head_counts(flat_out, layers, heads, N, K, counts_out, (hipStream_t)stream));
+  return PROXYKV_OK;
+}
+
+int proxykv_compact_pooled(proxykv_ctx* ctx, void* k, void* v, const int32_t* flat, const int32_t* counts, int64_t layers,
+                           int64_t heads, int64_t N, int64_t K, int64_t D, void* stream) {
+  if (!ctx || !k || !v || !flat || !counts) return PROXYKV_EINVAL;
+  if (layers <= 0 || heads <= 0 || N <= 0 || K < 1 || K > N || D <= 0) return PROXYKV_EINVAL;
+  if (layers * heads >= (1ll << 31) || heads * N >= (1ll << 31) - 4096) return PROXYKV_EINVAL;
+  if ((D * 2) % 16 != 0 || D * 2 > 512) return PROXYKV_EUNSUPPORTED;
+  PKV_HIP(ctx, hipSetDevice(ctx->cfg.device));
+  PKV_HIP(ctx, pkv::launch_compact_inplace(k, v, flat, layers * heads, N, K, D * 2, counts, (int)heads, (hipStream_t)stream));
   return PROXYKV_OK;
 }
 

@@ -53,11 +53,24 @@ __global__ __launch_bounds__(256) void compact_kernel(const u32x4* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 constexpr int kInplaceTokens = 128;
 
+// With counts != nullptr the rows are ragged (a budget shared by the `heads` rows of a layer): idx holds,
+// per layer, heads * K flat indices h * N + n in ascending order, row r = (layer, h) keeps counts[r] of
+// them, and its list starts behind those of the layer's earlier heads.
 template <int PER>  // 16-byte pieces per thread and chunk, for each of K and V
 __global__ __launch_bounds__(256) void compact_inplace_kernel(u32x4* __restrict__ k, u32x4* __restrict__ v,
-                                                               const int32_t* __restrict__ idx, int64_t N, int K, int cpr) {
+                                                               const int32_t* __restrict__ idx, int64_t N, int K, int cpr,
+                                                               const int32_t* __restrict__ counts, int heads) {
   const int r = blockIdx.x, tid = threadIdx.x;
   const int32_t* ridx = idx + (size_t)r * K;
+  int32_t sub = 0;  // what a stored index is ahead of the row's token number
+  if (counts != nullptr) {
+    const int layer = r / heads, h = r % heads;
+    int start = 0;
+    for (int hh = 0; hh < h; ++hh) start += counts[layer * heads + hh];
+    ridx = idx + (size_t)layer * heads * K + start;
+    K = counts[r];
+    sub = (int32_t)(h * N);
+  }
   u32x4* kb = k + (size_t)r * N * cpr;
   u32x4* vb = v + (size_t)r * N * cpr;
   const int n_chunks = (K + kInplaceTokens - 1) / kInplaceTokens;
@@ -67,7 +80,7 @@ __global__ __launch_bounds__(256) void compact_inplace_kernel(u32x4* __restrict_
     for (int u = 0; u < PER; ++u) {
       const int piece = tid + 256 * u, j = c * kInplaceTokens + piece / cpr, ch = piece % cpr;
       if (piece < kInplaceTokens * cpr && j < K) {
-        const size_t src = (size_t)ridx[j] * cpr + ch;
+        const size_t src = (size_t)(ridx[j] - sub) * cpr + ch;
         kr[u] = __builtin_nontemporal_load(kb + src);
         vr[u] = __builtin_nontemporal_load(vb + src);
       }
@@ -117,6 +130,26 @@ __global__ __launch_bounds__(256) void mask_kernel(const int32_t* __restrict__ i
   for (int j = tid; j < K; j += 256) row[ridx[j]] = 1;
 }
 
+// counts[layer, h] = number of a layer's kept flat indices (ascending, heads * K of them) that fall into
+// [h * N, (h + 1) * N): the difference of two lower bounds.  One thread per (layer, head).
+__global__ void head_counts_kernel(const int32_t* __restrict__ flat, int layers, int heads, int64_t N, int K,
+                                   int32_t* __restrict__ counts) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= layers * heads) return;
+  const int layer = t / heads, h = t % heads, n = heads * K;
+  const int32_t* row = flat + (size_t)layer * n;
+  auto lower_bound = [&](int64_t value) {  // first position whose index is >= value
+    int lo = 0, hi = n;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if ((int64_t)row[mid] < value) lo = mid + 1;
+      else hi = mid;
+    }
+    return lo;
+  };
+  counts[t] = lower_bound((int64_t)(h + 1) * N) - lower_bound((int64_t)h * N);
+}
+
 }  // namespace
 
 hipError_t launch_compact(const void* k_in, const void* v_in, const int32_t* idx, int64_t rows, int64_t N, int64_t K,
@@ -131,15 +164,23 @@ hipError_t launch_compact(const void* k_in, const void* v_in, const int32_t* idx
 }
 
 hipError_t launch_compact_inplace(void* k, void* v, const int32_t* idx, int64_t rows, int64_t N, int64_t K, int64_t row_bytes,
-                                  hipStream_t stream) {
+                                  const int32_t* counts, int heads, hipStream_t stream) {
   if (rows <= 0 || K <= 0) return hipSuccess;
   const int cpr = (int)(row_bytes / 16);
   const int per = (kInplaceTokens * cpr + 255) / 256;  // 16-byte pieces per thread and chunk
   u32x4 *kp = (u32x4*)k, *vp = (u32x4*)v;
-  if (per <= 4) compact_inplace_kernel<4><<<(unsigned)rows, 256, 0, stream>>>(kp, vp, idx, N, (int)K, cpr);
-  else if (per <= 8) compact_inplace_kernel<8><<<(unsigned)rows, 256, 0, stream>>>(kp, vp, idx, N, (int)K, cpr);
-  else if (per <= 16) compact_inplace_kernel<16><<<(unsigned)rows, 256, 0, stream>>>(kp, vp, idx, N, (int)K, cpr);
+  if (per <= 4) compact_inplace_kernel<4><<<(unsigned)rows, 256, 0, stream>>>(kp, vp, idx, N, (int)K, cpr, counts, heads);
+  else if (per <= 8) compact_inplace_kernel<8><<<(unsigned)rows, 256, 0, stream>>>(kp, vp, idx, N, (int)K, cpr, counts, heads);
+  else if (per <= 16) compact_inplace_kernel<16><<<(unsigned)rows, 256, 0, stream>>>(kp, vp, idx, N, (int)K, cpr, counts, heads);
   else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_head_counts(const int32_t* flat, int64_t layers, int64_t heads, int64_t N, int64_t K, int32_t* counts,
+                              hipStream_t stream) {
+  const int64_t n = layers * heads;
+  if (n <= 0) return hipSuccess;
+  head_counts_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(flat, (int)layers, (int)heads, N, (int)K, counts);
   return hipGetLastError();
 }
 

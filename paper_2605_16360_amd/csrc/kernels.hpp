@@ -30,7 +30,10 @@ hipError_t launch_compact(const void* k_in, const void* v_in, const int32_t* idx
 
 // In-place variant: tokens 0 .. K-1 of every row of k and v become the kept tokens in order.
 hipError_t launch_compact_inplace(void* k, void* v, const int32_t* idx, int64_t rows, int64_t N, int64_t K, int64_t row_bytes,
-                                  hipStream_t stream);
+                                  const int32_t* counts, int heads, hipStream_t stream);
+// counts [layers, heads] from a layer's ascending flat indices h * N + n (heads * K per layer)
+hipError_t launch_head_counts(const int32_t* flat, int64_t layers, int64_t heads, int64_t N, int64_t K, int32_t* counts,
+                              hipStream_t stream);
 // mask[r, n] = 1 if n is one of idx[r, :], else 0.
 hipError_t launch_mask(const int32_t* idx, int64_t rows, int64_t N, int64_t K, uint8_t* mask, hipStream_t stream);
 }  // namespace pkv

@@ -96,6 +96,12 @@ def test_argument_checks_run_before_any_device_call():
     assert lib.proxykv_compact_inplace(h, one, one, one, 1, 8, 2, 1024, None) == pk.PROXYKV_EUNSUPPORTED
     assert lib.proxykv_mask(h, one, 1, 8, 0, one, None) == pk.PROXYKV_EINVAL
     assert lib.proxykv_mask(h, one, 1, 8, 2, None, None) == pk.PROXYKV_EINVAL
+    assert lib.proxykv_topk_pooled(h, one, 1, 2, 8, 9, one, one, None) == pk.PROXYKV_EINVAL
+    assert lib.proxykv_topk_pooled(h, one, 1, 2, 8, 2, one, None, None) == pk.PROXYKV_EINVAL
+    assert lib.proxykv_topk_pooled(h, one, 1, 4096, 1 << 20, 2, one, one, None) == pk.PROXYKV_EINVAL   # heads * N too long
+    assert lib.proxykv_compact_pooled(h, one, one, one, None, 1, 2, 8, 2, 128, None) == pk.PROXYKV_EINVAL
+    assert lib.proxykv_compact_pooled(h, one, one, one, one, 1, 0, 8, 2, 128, None) == pk.PROXYKV_EINVAL
+    assert lib.proxykv_compact_pooled(h, one, one, one, one, 1, 2, 8, 2, 1024, None) == pk.PROXYKV_EUNSUPPORTED
     K = ctypes.c_int64()
     assert lib.proxykv_prune(h, one, one, one, 0, 8, 8, 4, 0.0, one, one, one, one, one, None, None,
                              ctypes.byref(K), None) == pk.PROXYKV_EINVAL

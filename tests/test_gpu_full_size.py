@@ -161,6 +161,26 @@ def _check_topk_compact(case, ctx, keep_ratio, rows_sampled=6):
             assert torch.equal(inplace[l:l + 1, h:h + 1, :K].cpu().view(torch.int16), exp.view(torch.int16)), (case.name, l, h)
             assert torch.equal(inplace[l, h, K:].view(torch.int16), src[l, h, K:].view(torch.int16)), (case.name, l, h)
     del k_ip, v_ip
+    # one budget per layer shared by its heads: selection against the oracle on every layer, the ragged
+    # compaction on the sampled rows
+    s3 = s.view(case.L_l, case.H_l, N)
+    s3[0, 0] += 1.0                                    # moves budget between the heads of layer 0
+    flat, counts = pk.proxykv_topk_pooled(ctx, s3, K)
+    torch.cuda.synchronize()
+    flat_ref, counts_ref = oracle.topk_pooled(s3.cpu(), K)
+    assert torch.equal(flat.cpu(), flat_ref) and torch.equal(counts.cpu(), counts_ref), f"pooled top-k[{case.name}] differs"
+    assert int(counts_ref[0, 0]) > K
+    k_pl, v_pl = k_t.clone(), v_t.clone()
+    pk.proxykv_compact_pooled(ctx, k_pl, v_pl, flat, counts)
+    torch.cuda.synchronize()
+    starts = torch.cumsum(counts_ref, 1) - counts_ref
+    for (l, h) in sorted(picks):
+        c, st = int(counts_ref[l, h]), int(starts[l, h])
+        tok = (flat_ref[l, st:st + c].to(torch.int64) - h * N).cuda()
+        for src, got in ((k_t, k_pl), (v_t, v_pl)):
+            assert torch.equal(got[l, h, :c].view(torch.int16), src[l, h][tok].view(torch.int16)), (case.name, l, h)
+            assert torch.equal(got[l, h, c:].view(torch.int16), src[l, h, c:].view(torch.int16)), (case.name, l, h)
+    del k_pl, v_pl
     return k_t, v_t
 
 

@@ -92,6 +92,40 @@ def test_compact_inplace_and_mask_bit_exact():
         assert torch.equal(m.cpu(), oracle.mask(idx, N)), (N, K)
 
 
+def test_pooled_budget_bit_exact():
+    """One budget per layer shared by its heads: kept flat indices, per-head counts, and the ragged in-place
+    compaction, against the oracle.  Covers short rows (register-resident selection) and long ones, heads that
+    get nothing, a head that gets everything it has, ties across heads."""
+    ctx = _ctx(synth.CASES["tiny"])
+    g = torch.Generator().manual_seed(5)
+    for (L, H, N, D, K) in [(2, 4, 700, 128, 211), (1, 3, 130, 64, 130), (1, 1, 9, 128, 1), (3, 8, 6000, 128, 1800),
+                            (1, 2, 1537, 256, 300), (2, 5, 333, 64, 7)]:
+        s = torch.randn(L, H, N, generator=g)
+        s[0, 0] += 4.0                                  # head 0 of layer 0 takes as much as it can
+        if H > 2:
+            s[0, 2] -= 8.0                              # and head 2 gets nothing
+        if L > 1:
+            s[1] = torch.round(s[1] * 2) / 2            # ties across heads
+        flat_ref, counts_ref = oracle.topk_pooled(s, K)
+        flat, counts = pk.proxykv_topk_pooled(ctx, s.cuda(), K)
+        torch.cuda.synchronize()
+        assert torch.equal(flat.cpu(), flat_ref), (N, K)
+        assert torch.equal(counts.cpu(), counts_ref), (N, K)
+        kv = torch.randn(2, L, H, N, D, generator=g).to(torch.bfloat16)
+        k, v = kv[0].cuda(), kv[1].cuda()
+        pk.proxykv_compact_pooled(ctx, k, v, flat, counts)
+        torch.cuda.synchronize()
+        for l in range(L):
+            start = 0
+            for h in range(H):
+                c = int(counts_ref[l, h])
+                tok = (flat_ref[l, start:start + c].to(torch.int64) - h * N)
+                start += c
+                for got, src in ((k, kv[0]), (v, kv[1])):
+                    assert torch.equal(got[l, h, :c].cpu().view(torch.int16), src[l, h][tok].view(torch.int16)), (N, K, l, h)
+                    assert torch.equal(got[l, h, c:].cpu().view(torch.int16), src[l, h, c:].view(torch.int16)), (N, K, l, h)
+
+
 # ----------------------------------------------------------------------------------------------
 # scoring
 # ----------------------------------------------------------------------------------------------

@@ -101,3 +101,24 @@ def test_mask_marks_exactly_the_kept_tokens():
     # the mask selects the same rows, in the same order, as the gather
     kv = torch.randn(2, 3, 50, 4, generator=g)
     assert torch.equal(kv[M.bool()].view(2, 3, 17, 4), oracle.compact(kv, idx))
+
+
+def test_topk_pooled_matches_sort_over_pairs():
+    """Brute force over (head, token) pairs with Python's sort under the stated order."""
+    g = torch.Generator().manual_seed(13)
+    L, H, N, K = 3, 4, 23, 5
+    s = torch.randn(L, H, N, generator=g)
+    s[1] = torch.round(s[1] * 2) / 2          # ties across heads
+    s[2, 1] += 3.0                            # one head takes most of the budget
+    flat, counts = oracle.topk_pooled(s, K)
+    assert flat.shape == (L, H * K) and counts.shape == (L, H) and flat.dtype == torch.int32
+    for l in range(L):
+        pairs = sorted(((-float(s[l, h, n]), h * N + n) for h in range(H) for n in range(N)))[:H * K]
+        want = sorted(p[1] for p in pairs)
+        assert flat[l].tolist() == want
+        assert counts[l].tolist() == [sum(1 for f in want if f // N == h) for h in range(H)]
+        assert int(counts[l].sum()) == H * K
+    assert int(counts[2, 1]) > K              # the budget moved to the strong head
+    # equal scores everywhere: the lowest flat indices are kept, i.e. head 0 first
+    flat, counts = oracle.topk_pooled(torch.zeros(1, 3, 10), 4)
+    assert flat[0].tolist() == list(range(12)) and counts[0].tolist() == [10, 2, 0]
