@@ -182,6 +182,11 @@ def main():
                    "K": K, "proxy": [case.L_s, case.H_q, case.H_kv, case.d], "target": [case.L_l, case.H_l, case.D]},
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": achieved, "peak": peak_tflops, "unit": "TFLOP/s",
                      "frac": achieved / peak_tflops, "traffic": measured_traffic(case.name, dominant)},
+        # pass 1 seen from the vector ALU, which is what bounds it: per visited pair one fma (2 flop), one exp2, one add
+        # = 4 flop in 4 issue slots of a lane (exp2 runs at half rate); 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz slots/s
+        "roofline_alu": {"bound": "alu", "kernel": "score_lse", "achieved": 4 * f_lse / (2 * case.d) / (stage_ms["score_lse"] * 1e-3) / 1e12,
+                         "peak": 256 * 4 * 16 * 2.4e9 / 1e12, "unit": "TFLOP/s",
+                         "frac": 4 * f_lse / (2 * case.d) / (stage_ms["score_lse"] * 1e-3) / (256 * 4 * 16 * 2.4e9)},
         "stages_ms": stage_ms,
         "score_mfma_frac": (f_lse + f_col) / ((stage_ms["score_lse"] + stage_ms["score_colmax"]) * 1e-3) / 1e12 / peak_tflops,
         "topk_compact_hbm": {"bytes": b_topk + b_comp, "achieved": hbm_gbps, "peak": 8000.0, "unit": "GB/s",
