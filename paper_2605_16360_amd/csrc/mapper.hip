@@ -92,8 +92,8 @@ __global__ __launch_bounds__(256) void stem_conv1_kernel(const float* __restrict
 // The K steps of all tiles of a workgroup form one stream: two LDS stages of 64 KB and ONE barrier
 // per step.  A step is four phases of 8 MFMAs; the fragments of phase kk+1 are read from LDS between
 // the MFMAs of phase kk (phase 3 reads phase 0 of the next step, behind the barrier), step s+1 goes
-// from registers to LDS during phase 2 and step s+2 is fetched from global memory into registers
-// during phase 3 -- across tile boundaries, so the next tile's loads are in flight during an epilogue.
+// from registers to LDS during phase 2 and each register is refilled with its part of step s+2 right
+// behind that -- across tile boundaries, so the next tile's loads are in flight during an epilogue.
 // The issue order is written out and pinned with scheduling barriers.
 //
 // Tile order: blocks are dealt round-robin to the 8 XCDs by the hardware, so XCD x = block % 8 takes the
@@ -237,8 +237,11 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_kernel(const uint16_t* __rest
           if constexpr (kk < 3) read_frag(st, kk + 1, nxt, j);
           else read_frag(st_next, 0, nxt, j);
         }
-        if constexpr (kk == 2) st_next[sslot + 64 * 8 * j] = rg[j];
-        if constexpr (kk == 3) fetch_one(j);
+        if constexpr (kk == 2) {
+          // the register is refilled as soon as it is free: a whole step lies between a load and its use
+          st_next[sslot + 64 * 8 * j] = rg[j];
+          fetch_one(j);
+        }
         __builtin_amdgcn_sched_barrier(0);
       });
     });
