@@ -11,6 +11,7 @@ from .proxykv_oracle import (  # noqa: F401
     layer_pairing,
     window_spans,
     score,
+    score_self,
     score_unit,
     softmax_rows_unit,
     softmax_row,

@@ -207,6 +207,38 @@ def score(q_rec: torch.Tensor, k_ctx: torch.Tensor, k_rec: torch.Tensor, chunk: 
     return X
 
 
+def score_self(q: torch.Tensor, k: torch.Tensor, round_inputs: bool = True, rows_per_block: int = 1024) -> torch.Tensor:
+    """The proxy feature exactly as Sec. 3 (system overview) prints it: the
+    post-softmax attention of the proxy's OWN prefill accumulated over the query
+    axis, X[l, h, n] = sum_q Softmax(Q K^T / sqrt(d))[l, h, q, n].
+
+    q [L_s, H_q, N, d], k [L_s, H_kv, N, d]; returns X [L_s, H_kv, N].
+    Readings: the proxy is a decoder, so its prefill attention is causal (query
+    q sees keys n <= q); with grouped-query attention the G query heads that
+    read KV head h are summed as well, which gives the H_s = KV heads of the
+    problem formulation.  Rows are evaluated in blocks only to bound memory.
+    """
+    L_s, H_q, N, d = q.shape
+    H_kv = k.shape[1]
+    if H_q % H_kv:
+        raise ValueError("H_q must be a multiple of H_kv")
+    G = H_q // H_kv
+    scale = 1.0 / math.sqrt(d)
+    X = torch.zeros(L_s, H_kv, N, dtype=F64)
+    cols = torch.arange(N).view(1, -1)
+    for l in range(L_s):
+        for h in range(H_q):
+            qh = _maybe_round(q[l, h], round_inputs, "bf16")
+            kh = _maybe_round(k[l, h // G], round_inputs, "bf16")
+            for r0 in range(0, N, rows_per_block):
+                r1 = min(r0 + rows_per_block, N)
+                logits = (qh[r0:r1] @ kh.T) * scale
+                rows = torch.arange(r0, r1).view(-1, 1)
+                logits = torch.where(cols <= rows, logits, torch.full_like(logits, -math.inf))
+                X[l, h // G] += torch.softmax(logits, dim=1).sum(dim=0)
+    return X
+
+
 # --------------------------------------------------------------------------
 # O2  HybridAxialMapper forward
 # --------------------------------------------------------------------------

@@ -214,3 +214,46 @@ def test_keep_count_and_layer_pairing_and_windows():
         assert (cover[:min(N, 1024)] == 1).all()
     assert len(oracle.window_spans(32768)) == 31 and sum(e - s for s, e in oracle.window_spans(32768)) == 63488
     assert len(oracle.window_spans(170000)) == 166 and sum(e - s for s, e in oracle.window_spans(170000)) == 338960
+
+
+# --------------------------------------------------------------------------
+# score_self: the feature as Sec. 3 prints it (causal self-attention, summed over the query axis)
+# --------------------------------------------------------------------------
+
+def test_score_self_matches_brute_force_loops():
+    """Per-row Python loops with math.exp: query i sees keys 0..i of its KV head."""
+    L, H_q, H_kv, N, d = 2, 4, 2, 11, 4
+    q, k = _rand((L, H_q, N, d), 71), _rand((L, H_kv, N, d), 72)
+    got = oracle.score_self(q, k, round_inputs=False, rows_per_block=4)
+    G = H_q // H_kv
+    want = np.zeros((L, H_kv, N))
+    for l in range(L):
+        for h in range(H_q):
+            for i in range(N):
+                logits = [float(np.dot(q[l, h, i], k[l, h // G, n])) / math.sqrt(d) for n in range(i + 1)]
+                top = max(logits)
+                Z = sum(math.exp(v - top) for v in logits)
+                for n in range(i + 1):
+                    want[l, h // G, n] += math.exp(logits[n] - top) / Z
+    assert np.allclose(got.numpy(), want, rtol=1e-12, atol=1e-14)
+
+
+def test_score_self_closed_forms_and_invariants():
+    # zero queries: row i spreads 1 / (i + 1) over keys 0..i, so X[n] = G (H_N - H_n) with harmonic numbers H
+    L, H_q, H_kv, N, d = 1, 6, 2, 9, 8
+    k = _rand((L, H_kv, N, d), 73)
+    X = oracle.score_self(torch.zeros(L, H_q, N, d, dtype=torch.float64), k, round_inputs=False)
+    G = H_q // H_kv
+    harmonic = [sum(1.0 / j for j in range(1, m + 1)) for m in range(N + 1)]
+    want = torch.tensor([G * (harmonic[N] - harmonic[n]) for n in range(N)], dtype=torch.float64)
+    assert torch.allclose(X[0, 0], want, rtol=1e-13) and torch.allclose(X[0, 1], want, rtol=1e-13)
+    # every row of every head is a probability vector: the scores of one KV head add up to G * N;
+    # the last key is seen by the last query only, the first key by every query
+    q = _rand((L, H_q, N, d), 74)
+    X = oracle.score_self(q, k, round_inputs=False)
+    assert torch.allclose(X.sum(dim=-1), torch.full((L, H_kv), float(G * N), dtype=torch.float64), rtol=1e-13)
+    assert bool((X[..., -1] <= G).all()) and bool((X[..., 0] >= G * 1.0).all())   # row 0 gives key 0 all its mass
+    # one token: the only probability is one
+    assert torch.equal(oracle.score_self(q[:, :, :1], k[:, :, :1], round_inputs=False), torch.full((L, H_kv, 1), float(G), dtype=torch.float64))
+    # inputs are rounded to bf16 first when asked
+    assert torch.equal(oracle.score_self(q, k), oracle.score_self(oracle.round_bf16(q), oracle.round_bf16(k), round_inputs=False))
