@@ -242,7 +242,10 @@ def main():
         flat = torch.empty(case.L_l, case.H_l * K, dtype=torch.int32, device=dev)
         counts = torch.empty(case.L_l, case.H_l, dtype=torch.int32, device=dev)
         k_pl, v_pl = k_t.clone(), v_t.clone()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+        # the feature as Sec. 3 prints it (causal self-attention of the sequence, summed over the queries)
+        x_self = torch.empty_like(x)
+        pk.proxykv_score_self(ctx, q, kr, x_out=x_self, stream=stream)      # warm-up
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
         torch.cuda.synchronize()
         ev[0].record()
         pk.proxykv_compact_inplace(ctx, k_ip, v_ip, idx, stream=stream)
@@ -253,11 +256,14 @@ def main():
         ev[3].record()
         pk.proxykv_compact_pooled(ctx, k_pl, v_pl, flat, counts, stream=stream)
         ev[4].record()
+        pk.proxykv_score_self(ctx, q, kr, x_out=x_self, stream=stream)
+        ev[5].record()
         torch.cuda.synchronize()
         out["extras_ms"] = {"compact_inplace": ev[0].elapsed_time(ev[1]), "mask": ev[1].elapsed_time(ev[2]),
                             "topk_pooled": ev[2].elapsed_time(ev[3]), "compact_pooled": ev[3].elapsed_time(ev[4]),
-                            "pooled_counts_min_max": [int(counts.min()), int(counts.max())]}
-        del k_ip, v_ip, m, k_pl, v_pl, y
+                            "pooled_counts_min_max": [int(counts.min()), int(counts.max())],
+                            "score_self": ev[4].elapsed_time(ev[5])}
+        del k_ip, v_ip, m, k_pl, v_pl, y, x_self
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(case, args.keep_ratio, x[0].float().cpu())
     print(json.dumps(out))

@@ -123,6 +123,16 @@ int proxykv_layer_pairing(const proxykv_config* cfg, int32_t* pairing_host);
 int proxykv_score(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const void* k_rec,
                   int32_t dtype, int64_t N, int64_t N_q, int32_t chunk, float* x_out, void* stream);
 
+/* The proxy feature in the form Sec. 3 (system overview) prints: the post-softmax attention of the
+ * proxy's own prefill accumulated over the query axis,
+ *   x_out[l, g, n] = sum over the heads h of group g and the queries i >= n of
+ *                    softmax_{j <= i}(<q_i, k_j> / sqrt(d))[n]
+ * (causal, as in a decoder's prefill; the G query heads of a KV head are summed).
+ *   q [L_s, H_q, N, d], k [L_s, H_kv, N, d] (DEVICE, dtype as in proxykv_score); x_out [L_s, H_kv, N] fp32.
+ * The scores of one (layer, KV head) add up to G * N.  The reduce field of the config is not used. */
+int proxykv_score_self(proxykv_ctx* ctx, const void* q, const void* k, int32_t dtype, int64_t N,
+                       float* x_out, void* stream);
+
 /* HybridAxialMapper forward (Sec. 4.1): x [L_s, H_kv, N] fp32 -> yhat [L_l, H_l, N] fp32 raw logits.
  * Target layer l_l reads proxy layer pairing[l_l]; weights are shared, so target layers paired with
  * the same proxy layer receive identical rows and the network runs once per distinct proxy layer.

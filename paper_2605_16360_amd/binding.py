@@ -20,7 +20,7 @@ PROXYKV_REDUCE_MAX, PROXYKV_REDUCE_SUM = 0, 1
 EXPORTS = [
     "proxykv_default_mapper", "proxykv_create", "proxykv_destroy", "proxykv_mapper_weight_count",
     "proxykv_set_mapper_weights", "proxykv_workspace_bytes", "proxykv_reserve", "proxykv_keep_count",
-    "proxykv_layer_pairing", "proxykv_score", "proxykv_map", "proxykv_topk", "proxykv_compact", "proxykv_compact_inplace",
+    "proxykv_layer_pairing", "proxykv_score", "proxykv_score_self", "proxykv_map", "proxykv_topk", "proxykv_compact", "proxykv_compact_inplace",
     "proxykv_mask", "proxykv_topk_pooled", "proxykv_compact_pooled", "proxykv_prune",
     "proxykv_profile_enable", "proxykv_profile_read", "proxykv_strerror", "proxykv_last_hip_error",
 ]
@@ -66,6 +66,7 @@ def load() -> ctypes.CDLL:
     lib.proxykv_keep_count.argtypes = [i64, f64, ctypes.POINTER(i64)]
     lib.proxykv_layer_pairing.argtypes = [cfgp, ctypes.POINTER(i32)]
     lib.proxykv_score.argtypes = [vp, vp, vp, vp, i32, i64, i64, i32, vp, vp]
+    lib.proxykv_score_self.argtypes = [vp, vp, vp, i32, i64, vp, vp]
     lib.proxykv_map.argtypes = [vp, vp, i64, vp, vp]
     lib.proxykv_topk.argtypes = [vp, vp, i64, i64, i64, vp, vp]
     lib.proxykv_compact.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp, vp]
@@ -237,6 +238,18 @@ def proxykv_score(ctx: Context, q_rec, k_ctx, k_rec, chunk: int, x_out=None, str
     _check(load().proxykv_score(ctx.handle, _dev_ptr(q_rec, "q_rec"), _dev_ptr(k_ctx, "k_ctx"), _dev_ptr(k_rec, "k_rec"),
                                 _qk_dtype(q_rec), N, N_q, chunk, _dev_ptr(x_out, "x_out", torch.float32),
                                 _stream_ptr(stream)), "proxykv_score", ctx.handle)
+    return x_out
+
+
+def proxykv_score_self(ctx: Context, q, k, x_out=None, stream=None) -> torch.Tensor:
+    """Causal self-attention probabilities summed over the query axis: q [L_s, H_q, N, d], k [L_s, H_kv, N, d]."""
+    c = ctx.cfg
+    N = q.shape[2]
+    assert q.shape == (c.L_s, c.H_q, N, c.d) and k.shape == (c.L_s, c.H_kv, N, c.d) and q.dtype == k.dtype
+    if x_out is None:
+        x_out = torch.empty(c.L_s, c.H_kv, N, dtype=torch.float32, device=q.device)
+    _check(load().proxykv_score_self(ctx.handle, _dev_ptr(q, "q"), _dev_ptr(k, "k"), _qk_dtype(q), N,
+                                     _dev_ptr(x_out, "x_out", torch.float32), _stream_ptr(stream)), "proxykv_score_self", ctx.handle)
     return x_out
 
 

@@ -207,9 +207,36 @@ int score_impl(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const voi
   PKV_HIP(ctx, pkv::launch_score_lse(q, kc, kr, nl, c.L_s, c.H_q, c.H_kv, c.d, N, N_q, chunk, stream));
   if ((rcm = mark(ctx, 1, stream))) return rcm;
   if (c.reduce == PROXYKV_REDUCE_SUM)
-    PKV_HIP(ctx, pkv::launch_score_colsum(q, kc, nl, x_out, c.L_s, c.H_q, c.H_kv, c.d, N, N_q, stream));
+    PKV_HIP(ctx, pkv::launch_score_colsum(q, kc, nl, x_out, c.L_s, c.H_q, c.H_kv, c.d, N, N_q, false, stream));
   else
     PKV_HIP(ctx, pkv::launch_score_colmax(q, kc, nl, x_out, c.L_s, c.H_q, c.H_kv, c.d, N, N_q, stream));
+  if ((rcm = mark(ctx, 2, stream))) return rcm;
+  return PROXYKV_OK;
+}
+
+// causal self-attention, summed over the query axis: pass 1 with no context keys and one chunk that spans the
+// sequence (query i sees its own keys j <= i), then the causal column sum
+int score_self_impl(proxykv_ctx* ctx, const void* q_in, const void* k_in, int32_t dtype, int64_t N, float* x_out,
+                    hipStream_t stream) {
+  const proxykv_config& c = ctx->cfg;
+  const uint16_t *q = (const uint16_t*)q_in, *k = (const uint16_t*)k_in;
+  int rc;
+  if (dtype == PROXYKV_FP32) {
+    const size_t nq = (size_t)c.L_s * c.H_q * (size_t)N * c.d, nk = (size_t)c.L_s * c.H_kv * (size_t)N * c.d;
+    if ((rc = ensure(ctx, ctx->q_bf16, nq * 2, stream))) return rc;
+    if ((rc = ensure(ctx, ctx->krec_bf16, nk * 2, stream))) return rc;
+    PKV_HIP(ctx, pkv::launch_f32_to_bf16((const float*)q_in, (uint16_t*)ctx->q_bf16.ptr, (int64_t)nq, stream));
+    PKV_HIP(ctx, pkv::launch_f32_to_bf16((const float*)k_in, (uint16_t*)ctx->krec_bf16.ptr, (int64_t)nk, stream));
+    q = (const uint16_t*)ctx->q_bf16.ptr;
+    k = (const uint16_t*)ctx->krec_bf16.ptr;
+  }
+  if ((rc = reserve_all(ctx, N, N, true, false, false, stream))) return rc;
+  float* nl = (float*)ctx->neg_lse.ptr;
+  int rcm;
+  if ((rcm = mark(ctx, 0, stream))) return rcm;
+  PKV_HIP(ctx, pkv::launch_score_lse(q, k, k, nl, c.L_s, c.H_q, c.H_kv, c.d, 0, N, (int)N, stream));
+  if ((rcm = mark(ctx, 1, stream))) return rcm;
+  PKV_HIP(ctx, pkv::launch_score_colsum(q, k, nl, x_out, c.L_s, c.H_q, c.H_kv, c.d, N, N, true, stream));
   if ((rcm = mark(ctx, 2, stream))) return rcm;
   return PROXYKV_OK;
 }
@@ -440,6 +467,15 @@ int proxykv_score(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const 
   if (rc) return rc;
   PKV_HIP(ctx, hipSetDevice(ctx->cfg.device));
   return score_impl(ctx, q_rec, k_ctx, k_rec, dtype, N, N_q, chunk, x_out, (hipStream_t)stream);
+}
+
+int proxykv_score_self(proxykv_ctx* ctx, const void* q, const void* k, int32_t dtype, int64_t N, float* x_out, void* stream) {
+  if (!ctx || !q || !k || !x_out) return PROXYKV_EINVAL;
+  if (dtype != PROXYKV_BF16 && dtype != PROXYKV_FP32) return PROXYKV_EINVAL;
+  const int rc = validate_lengths(N, N, N);
+  if (rc) return rc;
+  PKV_HIP(ctx, hipSetDevice(ctx->cfg.device));
+  return score_self_impl(ctx, q, k, dtype, N, x_out, (hipStream_t)stream);
 }
 
 int proxykv_map(proxykv_ctx* ctx, const float* x, int64_t N, float* yhat, void* stream) {

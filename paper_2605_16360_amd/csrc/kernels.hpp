@@ -19,8 +19,9 @@ hipError_t launch_score_colmax(const uint16_t* q, const uint16_t* k_ctx, const f
                                hipStream_t stream);
 
 // Scoring, pass 2 in the sum form: x[l, g, n] = sum over (head of group g, query i) of 2^(c * (<q_i, k_n> + neg_lse[l, h, i])).
+// causal: the keys are the queries' own sequence (N == N_q) and query i adds to keys n <= i only.
 hipError_t launch_score_colsum(const uint16_t* q, const uint16_t* k_ctx, const float* neg_lse, float* x,
-                               int L_s, int H_q, int H_kv, int d, int64_t N, int64_t N_q,
+                               int L_s, int H_q, int H_kv, int d, int64_t N, int64_t N_q, bool causal,
                                hipStream_t stream);
 hipError_t launch_topk(const float* scores, int64_t rows, int64_t N, int64_t K, int32_t* idx_out,
                        hipStream_t stream);

@@ -179,7 +179,10 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void score_colmax_kernel(con
 // and added: mul, exp2, add per element, so this kernel is bound by the vector ALU like pass 1.  A probability
 // never exceeds one, so there is no reference to track.  Rows past N_q carry -inf and add zero.
 // ---------------------------------------------------------------------------------------------
-template <int D, int NCOL>
+//
+// CAUSAL: the proxy's own prefill attention (N_q == N, the keys are the sequence's own): query i sees keys n <= i, so a
+// workgroup starts at the query tile that holds its first key and masks the tiles that the diagonal cuts.
+template <int D, int NCOL, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void score_colsum_kernel(const uint16_t* __restrict__ q,
                                                                const uint16_t* __restrict__ k_ctx,
                                                                const float* __restrict__ neg_lse,
@@ -209,10 +212,11 @@ __global__ __launch_bounds__(256, 2) void score_colsum_kernel(const uint16_t* __
 
   // tiles are fetched in order: head g = 0..G-1 of the group, query tile qt = 0..nqt-1
   const int nqt = (N_q + C::ROWS - 1) / C::ROWS;
-  const int total = G * nqt;
+  const int qt_first = CAUSAL ? n0 / C::ROWS : 0;  // KB is a multiple of ROWS
+  const int total = G * (nqt - qt_first);
   TileRegs<D> regs;
   float nl_reg = kNegInf;
-  int fg = 0, fqt = 0;
+  int fg = 0, fqt = qt_first;
   auto fetch_next = [&]() {
     const size_t head = (size_t)(l * H_q + hs * G + fg);
     tile_fetch<D>(regs, q + head * N_q * D, fqt * C::ROWS, N_q, tid);
@@ -221,7 +225,7 @@ __global__ __launch_bounds__(256, 2) void score_colsum_kernel(const uint16_t* __
       nl_reg = i < N_q ? neg_lse[head * N_q + i] : kNegInf;
     }
     if (++fqt == nqt) {
-      fqt = 0;
+      fqt = qt_first;
       ++fg;
     }
   };
@@ -237,6 +241,7 @@ __global__ __launch_bounds__(256, 2) void score_colsum_kernel(const uint16_t* __
   }
   if (total > 2) fetch_next();
 
+  int cqt = qt_first;  // query tile of step t
   for (int t = 0; t < total; ++t) {
     // every wave has finished tile t-1: its buffer takes tile t+2, the registers take tile t+3
     __syncthreads();
@@ -244,6 +249,9 @@ __global__ __launch_bounds__(256, 2) void score_colsum_kernel(const uint16_t* __
     if (t + 3 < total) fetch_next();
     const u32x4* buf = lds + (t % kNBuf) * C::TILE_U4;
     const float* nl = lds_nl + (t % kNBuf) * C::ROWS;
+    const int row0 = cqt * C::ROWS;
+    const bool diag = CAUSAL && row0 < n0 + KB - 1;  // some query of the tile lies before some key of the block
+    if (++cqt == nqt) cqt = qt_first;
 #pragma unroll
     for (int s = 0; s < C::SUB; ++s) {
       bf16x8 a[C::KK];
@@ -267,6 +275,15 @@ __global__ __launch_bounds__(256, 2) void score_colsum_kernel(const uint16_t* __
           acc[e] = init;
 #pragma unroll
           for (int kk = 0; kk < C::KK; ++kk) acc[e] = mfma_32x32x16(a[kk], b[cp + e][kk], acc[e]);
+        }
+        if (diag) {
+#pragma unroll
+          for (int e = 0; e < 2; ++e)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int i = row0 + s * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+              acc[e][r] = i >= kn[cp + e] ? acc[e][r] : kNegInf;
+            }
         }
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
@@ -306,13 +323,20 @@ hipError_t launch_f32_to_bf16(const float* in, uint16_t* out, int64_t n, hipStre
 }
 
 hipError_t launch_score_colsum(const uint16_t* q, const uint16_t* k_ctx, const float* neg_lse, float* x, int L_s,
-                               int H_q, int H_kv, int d, int64_t N, int64_t N_q, hipStream_t stream) {
+                               int H_q, int H_kv, int d, int64_t N, int64_t N_q, bool causal, hipStream_t stream) {
   const int G = H_q / H_kv;
   const float c = 1.4426950408889634f / sqrtf((float)d);
   constexpr int NCOL = 2;
+  if (causal && N != N_q) return hipErrorInvalidValue;
   dim3 grid((unsigned)((N + 128 * NCOL - 1) / (128 * NCOL)), (unsigned)H_kv, (unsigned)L_s);
-  if (d == 64) score_colsum_kernel<64, NCOL><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, (int)N, (int)N_q, c);
-  else score_colsum_kernel<128, NCOL><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, (int)N, (int)N_q, c);
+  const int n = (int)N, nq = (int)N_q;
+  if (d == 64) {
+    if (causal) score_colsum_kernel<64, NCOL, true><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, n, nq, c);
+    else score_colsum_kernel<64, NCOL, false><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, n, nq, c);
+  } else {
+    if (causal) score_colsum_kernel<128, NCOL, true><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, n, nq, c);
+    else score_colsum_kernel<128, NCOL, false><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, n, nq, c);
+  }
   return hipGetLastError();
 }
 

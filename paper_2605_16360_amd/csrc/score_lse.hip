@@ -123,7 +123,7 @@ __global__ __launch_bounds__(256, MINB) void score_lse_kernel(const uint16_t* __
     }
     return (s0 + s1) + (s2 + s3);
   };
-  // the keys of an interior context tile, visible to every query, summed without checks
+  // the keys of an interior tile, visible to every query of the block, summed without checks
   auto interior_tile = [&](const u32x4* buf) {
 #pragma unroll
     for (int s = 0; s < C::SUB; ++s) {
@@ -158,9 +158,11 @@ __global__ __launch_bounds__(256, MINB) void score_lse_kernel(const uint16_t* __
     const u32x4* buf = lds + (t % kNBuf) * C::TILE_U4;
     const bool is_rec = t >= n_ctx;
     const int row0 = is_rec ? rec_lo + (t - n_ctx) * C::ROWS : t * C::ROWS;
-    // interior context tile: summed without checks, and again chain by chain with them if a sum went out of
+    // interior tile: summed without checks, and again chain by chain with them if a sum went out of
     // range (the very first tile does: the reference starts at -1e30)
-    bool careful = is_rec || row0 + C::ROWS > N;
+    // a reconstruction tile is interior too when all its keys lie at or before the block's first query and inside the
+    // chunk of its last one (then inside every query's chunk)
+    bool careful = is_rec ? !(row0 + C::ROWS - 1 <= i0 && row0 >= ((i_end - 1) / chunk) * chunk) : (row0 + C::ROWS > N);
     if (!careful) {
       float before[NCOL];
 #pragma unroll

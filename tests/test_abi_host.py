@@ -83,6 +83,9 @@ def test_argument_checks_run_before_any_device_call():
     assert lib.proxykv_score(h, one, one, one, 5, 8, 8, 4, one, None) == pk.PROXYKV_EINVAL
     assert lib.proxykv_score(h, one, one, one, 0, 1 << 31, 8, 4, one, None) == pk.PROXYKV_EINVAL
     assert lib.proxykv_score(None, one, one, one, 0, 8, 8, 4, one, None) == pk.PROXYKV_EINVAL
+    assert lib.proxykv_score_self(h, one, None, 0, 8, one, None) == pk.PROXYKV_EINVAL
+    assert lib.proxykv_score_self(h, one, one, 0, 0, one, None) == pk.PROXYKV_EINVAL
+    assert lib.proxykv_score_self(h, one, one, 7, 8, one, None) == pk.PROXYKV_EINVAL
     assert lib.proxykv_map(h, one, 8, None, None) == pk.PROXYKV_EINVAL
     assert lib.proxykv_map(h, one, 8, one, None) == pk.PROXYKV_ESTATE          # weights not set
     assert lib.proxykv_topk(h, one, 1, 8, 0, one, None) == pk.PROXYKV_EINVAL

@@ -243,6 +243,24 @@ def test_llama_8k_sum_form_full_size():
     pk.proxykv_destroy(ctx)
 
 
+def test_llama_8k_score_self_full_size():
+    """The causal self-attention feature at full size: one whole (layer, KV head) unit key by key against the oracle;
+    on every unit the total over the keys equals the number of query rows (every row is a probability vector), the
+    last key holds what the last query gives itself (at most one per head), and nothing is negative."""
+    case = synth.CASES["llama_8k"]
+    ctx = pk.proxykv_create(pk.config_for_case(case))
+    q, _, k = synth.make_proxy_qk(case, device="cuda")
+    x = pk.proxykv_score_self(ctx, q, k)
+    torch.cuda.synchronize()
+    G, (l, h) = case.G, (9, 2)
+    ref = oracle.score_self(q[l:l + 1, h * G:(h + 1) * G].double().cpu(), k[l:l + 1, h:h + 1].double().cpu())[0, 0]
+    _close(x[l, h], ref, "score_self[llama_8k] unit (9, 2)")
+    tot = x.double().sum(dim=-1)
+    assert torch.allclose(tot, torch.full_like(tot, float(G * case.N_q)), rtol=1e-4)
+    assert float(x.min()) >= 0.0 and float(x[..., -1].max()) <= G * (1 + 1e-5)
+    pk.proxykv_destroy(ctx)
+
+
 def test_llama_32k_full_size():
     """The workload bench.py times."""
     N = synth.CASES["llama_32k"].N

@@ -173,6 +173,36 @@ def test_score_sum_form_matches_oracle(name):
     assert float(x.sum(dim=-1).max()) <= case.G * case.N_q * (1.0 + 1e-5)
 
 
+@pytest.mark.parametrize("name", list(SCORE_CASES))
+def test_score_self_matches_oracle(name):
+    """The feature as Sec. 3 prints it: causal self-attention of the sequence, summed over queries and group heads."""
+    case = _score_case(name)
+    q, _, k = synth.make_proxy_qk(case)                 # the reconstruction keys serve as the sequence's own keys
+    ref = oracle.score_self(q.double(), k.double())
+    ctx = _ctx(case)
+    x = pk.proxykv_score_self(ctx, q.cuda(), k.cuda())
+    torch.cuda.synchronize()
+    assert_close(x, ref, f"score_self[{name}]")
+    # every query row is a probability vector over its visible keys
+    total = x.double().sum(dim=-1).cpu()
+    assert torch.allclose(total, torch.full_like(total, float(case.G * case.N_q)), rtol=1e-4)
+
+
+def test_score_self_fp32_inputs_and_block_boundaries():
+    """fp32 inputs are rounded to bf16 on entry; lengths at and around the 256-key / 128-query tile sizes."""
+    base = synth.scaled_case(synth.CASES["llama_8k"], name="self_f32", L_s=1, H_q=2, H_kv=1, d=64, L_l=1, H_l=2, N=8, N_q=8, chunk=8,
+                             n_planted=0)
+    ctx = _ctx(base)
+    for N in (1, 2, 127, 128, 129, 255, 256, 257, 513):
+        g = torch.Generator().manual_seed(N)
+        q = torch.randn(1, 2, N, 64, generator=g)
+        k = torch.randn(1, 1, N, 64, generator=g)
+        ref = oracle.score_self(q, k)                   # the oracle rounds to bf16 itself
+        x = pk.proxykv_score_self(ctx, q.cuda(), k.cuda())
+        torch.cuda.synchronize()
+        assert_close(x, ref, f"score_self fp32 N={N}")
+
+
 def test_score_tiny_case_fp32_inputs_and_planted_keys():
     case = synth.CASES["tiny"]
     q, kc, kr = synth.make_proxy_qk(case)
