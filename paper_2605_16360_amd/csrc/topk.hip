@@ -31,18 +31,32 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
   __shared__ uint32_t s_prefix, s_krem;
   __shared__ uint32_t wave_gt[kTopkWaves], wave_eq[kTopkWaves];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  auto key_at = [&](int i) -> uint32_t { return order_key(row[i]); };
+  // f(key) for the keys tid, tid + 1024, ... of the row, sixteen loads in flight per thread (one workgroup per row:
+  // the loop is bound by the bytes it keeps in flight)
+  auto for_each_key = [&](auto&& f) {
+    constexpr int kBatch = 16;
+    for (int i0 = tid; i0 < N; i0 += kBatch * kTopkThreads) {
+      float v[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int i = i0 + u * kTopkThreads;
+        v[u] = row[i < N ? i : N - 1];
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u)
+        if (i0 + u * kTopkThreads < N) f(order_key(v[u]));
+    }
+  };
 
   // Range of the row's keys: the radix digits are taken from key - kmin, top-aligned to the width of the
   // range.  Digits of the raw key are badly skewed (scores share sign and exponent), and lanes that add to
   // the same LDS counter are serialised; digits of the range-relative key are spread over all 256 bins.
   __syncthreads();
   uint32_t kmin = 0xffffffffu, kmax = 0u;
-  for (int i = tid; i < N; i += kTopkThreads) {
-    const uint32_t key = key_at(i);
+  for_each_key([&](uint32_t key) {
     kmin = key < kmin ? key : kmin;
     kmax = key > kmax ? key : kmax;
-  }
+  });
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
     const uint32_t a = __shfl_xor(kmin, off, 64), c = __shfl_xor(kmax, off, 64);
@@ -70,10 +84,10 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
     const uint32_t dmask = (1u << (prev_sh - shift)) - 1u;
     for (int i = tid; i < kTopkWaves * 256; i += kTopkThreads) (&hist[0][0])[i] = 0;
     __syncthreads();
-    for (int i = tid; i < N; i += kTopkThreads) {
-      const uint32_t rel = key_at(i) - kmin;
+    for_each_key([&](uint32_t key) {
+      const uint32_t rel = key - kmin;
       if (first || (rel >> prev_sh) == prefix) atomicAdd(&hist[wave][(rel >> shift) & dmask], 1u);
-    }
+    });
     __syncthreads();
     if (tid < 256) {
       uint32_t s = 0;
@@ -113,40 +127,67 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(const float* __restr
   __syncthreads();
 
   // `prefix` is now the K-th largest key T; `krem` of the keys equal to T are kept, lowest index first.
+  // Ordered output without a barrier per tile: wave w owns the contiguous part [w * per_wave, (w + 1) * per_wave) of the
+  // row.  A first sweep counts the keys above T and equal to T in every part, one prefix sum over the 16 parts gives each
+  // wave its first output slot and the number of equal keys before it, and a second sweep writes the indices in order
+  // with a running offset that lives in the wave.
   const uint32_t T = prefix, eq_take = krem;
-  uint32_t base_out = 0, base_eq = 0;
-  for (int tile = 0; tile < N; tile += kTopkThreads) {
-    const int i = tile + tid;
-    const bool valid = i < N;
-    const uint32_t key = valid ? key_at(i) : 0u;
-    const bool gt = valid && key > T, eq = valid && key == T;
-    const uint64_t bg = __builtin_amdgcn_ballot_w64(gt), be = __builtin_amdgcn_ballot_w64(eq);
-    const uint64_t lower = (1ull << lane) - 1ull;
-    const uint32_t lane_gt = __popcll(bg & lower), lane_eq = __popcll(be & lower);
-    if (lane == 0) {
-      wave_gt[wave] = __popcll(bg);
-      wave_eq[wave] = __popcll(be);
-    }
-    __syncthreads();
-    uint32_t wg = 0, we = 0, tg = 0, te = 0;
+  const int per_wave = ((N + kTopkWaves - 1) / kTopkWaves + 63) & ~63;
+  const int w_lo = wave * per_wave < N ? wave * per_wave : N;
+  const int w_hi = w_lo + per_wave < N ? w_lo + per_wave : N;
+  uint32_t cnt_gt = 0, cnt_eq = 0;
+  for (int i0 = w_lo + lane; i0 < w_hi; i0 += 16 * 64) {
+    float v[16];
 #pragma unroll
-    for (int w = 0; w < kTopkWaves; ++w) {
-      const uint32_t g = wave_gt[w], e = wave_eq[w];
-      if (w < wave) {
-        wg += g;
-        we += e;
-      }
-      tg += g;
-      te += e;
+    for (int u = 0; u < 16; ++u) v[u] = row[i0 + u * 64 < w_hi ? i0 + u * 64 : w_hi - 1];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const uint32_t key = order_key(v[u]);
+      cnt_gt += (i0 + u * 64 < w_hi) && key > T;
+      cnt_eq += (i0 + u * 64 < w_hi) && key == T;
     }
-    const uint32_t eq_rank = base_eq + we + lane_eq;
-    const uint32_t taken_before_tile = base_eq < eq_take ? base_eq : eq_take;
-    const uint32_t taken_before_me = (eq_rank < eq_take ? eq_rank : eq_take) - taken_before_tile;
-    if (gt || (eq && eq_rank < eq_take)) out[base_out + wg + lane_gt + taken_before_me] = i;
-    const uint32_t eq_after = base_eq + te;
-    base_out += tg + ((eq_after < eq_take ? eq_after : eq_take) - taken_before_tile);
-    base_eq = eq_after;
-    __syncthreads();
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    cnt_gt += __shfl_xor(cnt_gt, off, 64);
+    cnt_eq += __shfl_xor(cnt_eq, off, 64);
+  }
+  if (lane == 0) {
+    wave_gt[wave] = cnt_gt;
+    wave_eq[wave] = cnt_eq;
+  }
+  __syncthreads();
+  uint32_t eq_before = 0, out_pos = 0;  // equal keys in earlier parts; first output slot of this part
+#pragma unroll
+  for (int w = 0; w < kTopkWaves; ++w) {
+    if (w < wave) {
+      const uint32_t e_after = eq_before + wave_eq[w];
+      out_pos += wave_gt[w] + ((e_after < eq_take ? e_after : eq_take) - (eq_before < eq_take ? eq_before : eq_take));
+      eq_before = e_after;
+    }
+  }
+  const uint64_t lower = (1ull << lane) - 1ull;
+  for (int base0 = w_lo; base0 < w_hi; base0 += 16 * 64) {
+    float v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int i = base0 + u * 64 + lane;
+      v[u] = row[i < w_hi ? i : w_hi - 1];
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int i = base0 + u * 64 + lane;
+      const bool valid = i < w_hi;  // once false for a wave's tile it stays false: the counts below add nothing
+      const uint32_t key = order_key(v[u]);
+      const bool gt = valid && key > T, eq = valid && key == T;
+      const uint64_t be = __builtin_amdgcn_ballot_w64(eq);
+      const uint32_t eq_rank = eq_before + __popcll(be & lower);
+      const bool take = gt || (eq && eq_rank < eq_take);
+      const uint64_t bt = __builtin_amdgcn_ballot_w64(take);
+      if (take) out[out_pos + __popcll(bt & lower)] = i;
+      out_pos += __popcll(bt);
+      eq_before += __popcll(be);
+    }
   }
 }
 
