@@ -27,7 +27,7 @@ namespace {
 
 // ---------------------------------------------------------------------------------------------
 // pass 2: x[l, hs, n] = 2^(c * max_{g, i} (<q^{(hs*G+g)}_i, k_n> + neg_lse[l, hs*G+g, i]))
-// grid (ceil(N / (128*NCOL)), H_kv, L_s), 256 threads; wave w owns context keys
+// one-dimensional grid over (KV group, key block of 128*NCOL keys), 256 threads; wave w owns context keys
 // [n0 + 32*NCOL*w, +32*NCOL) as the resident B operand and streams all G*N_q queries.
 // Rows past N_q carry -inf as their initial value, so every sub-tile is processed without a branch.
 // Chains are handled in pairs (two column sub-tiles): the MFMAs of pair i are issued while the
@@ -37,16 +37,19 @@ template <int D, int NCOL>
 __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void score_colmax_kernel(const uint16_t* __restrict__ q,
                                                                const uint16_t* __restrict__ k_ctx,
                                                                const float* __restrict__ neg_lse,
-                                                               float* __restrict__ x, int H_q, int G, int N, int N_q,
+                                                               float* __restrict__ x, int L_s, int H_q, int G, int N, int N_q,
                                                                float c) {
   using C = ScoreCfg<D>;
   static_assert(NCOL % 2 == 0, "column sub-tiles are processed in pairs");
   __shared__ u32x4 lds[kNBuf * C::TILE_U4];
   __shared__ __attribute__((aligned(16))) float lds_nl[kNBuf * C::ROWS];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
-  const int hs = blockIdx.y, l = blockIdx.z, H_kv = H_q / G;
   constexpr int KB = 128 * NCOL;
-  const int n0 = blockIdx.x * KB;
+  const int H_kv = H_q / G;
+  const GroupBlock gb = group_block((N + KB - 1) / KB);  // a group's blocks: its key blocks (they stream the same queries)
+  if (gb.group >= L_s * H_kv) return;
+  const int l = gb.group / H_kv, hs = gb.group % H_kv;
+  const int n0 = gb.item * KB;
   const uint16_t* kc = k_ctx + (size_t)(l * H_kv + hs) * N * D;
 
   bf16x8 b[NCOL][C::KK];
@@ -186,15 +189,18 @@ template <int D, int NCOL, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void score_colsum_kernel(const uint16_t* __restrict__ q,
                                                                const uint16_t* __restrict__ k_ctx,
                                                                const float* __restrict__ neg_lse,
-                                                               float* __restrict__ x, int H_q, int G, int N, int N_q,
+                                                               float* __restrict__ x, int L_s, int H_q, int G, int N, int N_q,
                                                                float c) {
   using C = ScoreCfg<D>;
   __shared__ u32x4 lds[kNBuf * C::TILE_U4];
   __shared__ __attribute__((aligned(16))) float lds_nl[kNBuf * C::ROWS];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
-  const int hs = blockIdx.y, l = blockIdx.z, H_kv = H_q / G;
   constexpr int KB = 128 * NCOL;
-  const int n0 = blockIdx.x * KB;
+  const int H_kv = H_q / G;
+  const GroupBlock gb = group_block((N + KB - 1) / KB);  // a group's blocks: its key blocks (they stream the same queries)
+  if (gb.group >= L_s * H_kv) return;
+  const int l = gb.group / H_kv, hs = gb.group % H_kv;
+  const int n0 = gb.item * KB;
   const uint16_t* kc = k_ctx + (size_t)(l * H_kv + hs) * N * D;
 
   bf16x8 b[NCOL][C::KK];
@@ -328,14 +334,15 @@ hipError_t launch_score_colsum(const uint16_t* q, const uint16_t* k_ctx, const f
   const float c = 1.4426950408889634f / sqrtf((float)d);
   constexpr int NCOL = 2;
   if (causal && N != N_q) return hipErrorInvalidValue;
-  dim3 grid((unsigned)((N + 128 * NCOL - 1) / (128 * NCOL)), (unsigned)H_kv, (unsigned)L_s);
+  const unsigned grid = group_grid((int64_t)L_s * H_kv, (N + 128 * NCOL - 1) / (128 * NCOL));
+  if (grid == 0) return hipErrorInvalidValue;
   const int n = (int)N, nq = (int)N_q;
   if (d == 64) {
-    if (causal) score_colsum_kernel<64, NCOL, true><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, n, nq, c);
-    else score_colsum_kernel<64, NCOL, false><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, n, nq, c);
+    if (causal) score_colsum_kernel<64, NCOL, true><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, L_s, H_q, G, n, nq, c);
+    else score_colsum_kernel<64, NCOL, false><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, L_s, H_q, G, n, nq, c);
   } else {
-    if (causal) score_colsum_kernel<128, NCOL, true><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, n, nq, c);
-    else score_colsum_kernel<128, NCOL, false><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, n, nq, c);
+    if (causal) score_colsum_kernel<128, NCOL, true><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, L_s, H_q, G, n, nq, c);
+    else score_colsum_kernel<128, NCOL, false><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, L_s, H_q, G, n, nq, c);
   }
   return hipGetLastError();
 }
@@ -346,12 +353,16 @@ hipError_t launch_score_colmax(const uint16_t* q, const uint16_t* k_ctx, const f
   const float c = 1.4426950408889634f / sqrtf((float)d);
   if (d == 64) {
     constexpr int NCOL = 4;
-    dim3 grid((unsigned)((N + 128 * NCOL - 1) / (128 * NCOL)), (unsigned)H_kv, (unsigned)L_s);
-    score_colmax_kernel<64, NCOL><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, (int)N, (int)N_q, c);
+    const unsigned grid = group_grid((int64_t)L_s * H_kv, (N + 128 * NCOL - 1) / (128 * NCOL));
+    if (grid == 0) return hipErrorInvalidValue;
+  if (grid == 0) return hipErrorInvalidValue;
+    score_colmax_kernel<64, NCOL><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, L_s, H_q, G, (int)N, (int)N_q, c);
   } else {
     constexpr int NCOL = 2;
-    dim3 grid((unsigned)((N + 128 * NCOL - 1) / (128 * NCOL)), (unsigned)H_kv, (unsigned)L_s);
-    score_colmax_kernel<128, NCOL><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, H_q, G, (int)N, (int)N_q, c);
+    const unsigned grid = group_grid((int64_t)L_s * H_kv, (N + 128 * NCOL - 1) / (128 * NCOL));
+    if (grid == 0) return hipErrorInvalidValue;
+  if (grid == 0) return hipErrorInvalidValue;
+    score_colmax_kernel<128, NCOL><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, L_s, H_q, G, (int)N, (int)N_q, c);
   }
   return hipGetLastError();
 }
