@@ -147,11 +147,14 @@ def main():
         step()
     torch.cuda.synchronize()
     stage_ms = {s: 0.0 for s in pk.STAGES}
+    step_event_ms = []                                      # per step: sum of its stage times (device time)
     t0 = time.perf_counter()
     for i in range(args.steps):
         step()
         note(f"step {i} enqueued")
-        for s, v in pk.proxykv_profile_read(ctx).items():   # HIP events recorded on the work stream
+        prof = pk.proxykv_profile_read(ctx)                 # HIP events recorded on the work stream
+        step_event_ms.append(sum(prof.values()))
+        for s, v in prof.items():
             stage_ms[s] += v / args.steps
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -188,6 +191,7 @@ def main():
                          "peak": 256 * 4 * 16 * 2.4e9 / 1e12, "unit": "TFLOP/s",
                          "frac": 4 * f_lse / (2 * case.d) / (stage_ms["score_lse"] * 1e-3) / (256 * 4 * 16 * 2.4e9)},
         "stages_ms": stage_ms,
+        "step_event_ms": {"min": min(step_event_ms), "median": sorted(step_event_ms)[len(step_event_ms) // 2]},
         "score_mfma_frac": (f_lse + f_col) / ((stage_ms["score_lse"] + stage_ms["score_colmax"]) * 1e-3) / 1e12 / peak_tflops,
         "topk_compact_hbm": {"bytes": b_topk + b_comp, "achieved": hbm_gbps, "peak": 8000.0, "unit": "GB/s",
                              "frac": hbm_gbps / 8000.0},
