@@ -58,10 +58,26 @@ def test_topk_bit_exact(N, K):
     assert torch.equal(got.cpu(), ref)
 
 
+@pytest.mark.parametrize("N", [36863, 36864, 36865, 40000])
+def test_topk_bit_exact_around_the_kernel_switch(N):
+    """Rows of up to 36 864 scores take the register-resident kernel, longer ones the streaming kernel."""
+    ctx = _ctx(synth.CASES["tiny"])
+    g = torch.Generator().manual_seed(N)
+    s = torch.randn(5, N, generator=g)
+    s[1] = torch.round(s[1] * 3) / 3
+    s[2] = -7.5
+    s[3, N // 2:] = s[3, :N - N // 2].clone()        # every value twice: the tie rule decides half of the cut
+    for K in (1, N // 3, N - 1, N):
+        got = pk.proxykv_topk(ctx, s.cuda(), K)
+        torch.cuda.synchronize()
+        assert torch.equal(got.cpu(), oracle.topk(s, K)), (N, K)
+
+
 def test_compact_bit_exact():
     ctx = _ctx(synth.CASES["tiny"])
     g = torch.Generator().manual_seed(3)
-    for (L, H, N, D, K) in [(2, 3, 700, 128, 211), (1, 2, 130, 64, 130), (1, 1, 9, 128, 1)]:
+    for (L, H, N, D, K) in [(2, 3, 700, 128, 211), (1, 2, 130, 64, 130), (1, 1, 9, 128, 1), (1, 2, 300, 256, 77), (2, 1, 257, 32, 100),
+                            (1, 1, 100, 8, 33)]:
         kv = torch.randn(2, L, H, N, D, generator=g).to(torch.bfloat16)
         s = torch.randn(L * H, N, generator=g)
         idx = oracle.topk(s, K).view(L, H, K)
@@ -313,3 +329,30 @@ def test_prune_tiny_case_end_to_end():
     k2, v2, idx2, _ = pk.proxykv_prune(ctx, q.cuda(), kc.cuda(), kr.cuda(), case.chunk, 0.3, k_t.cuda(), v_t.cuda())
     torch.cuda.synchronize()
     assert torch.equal(idx2, idx) and torch.equal(k2.view(torch.int16), k_out.view(torch.int16))
+
+
+def test_prune_with_the_sum_form_equals_its_stages():
+    """reduce = SUM through the fused call: same bits as score -> map -> top-k -> compact called one by one."""
+    case = synth.scaled_case(synth.CASES["llama_8k"], name="prune_sum", L_s=2, H_q=4, H_kv=2, d=64, L_l=3, H_l=2, N=700, N_q=500,
+                             chunk=200, n_planted=4)
+    q, kc, kr = synth.make_proxy_qk(case, device="cuda")
+    k_t, v_t = synth.make_target_kv(case, device="cuda")
+    w = synth.make_mapper_weights(case.H_kv, case.H_l)
+    cfg = pk.config_for_case(case)
+    cfg.reduce = pk.PROXYKV_REDUCE_SUM
+    ctx = pk.proxykv_create(cfg)
+    pk.proxykv_set_mapper_weights(ctx, w)
+    x = torch.empty(case.L_s, case.H_kv, case.N, dtype=torch.float32, device="cuda")
+    y = torch.empty(case.L_l, case.H_l, case.N, dtype=torch.float32, device="cuda")
+    k_out, v_out, idx, K = pk.proxykv_prune(ctx, q, kc, kr, case.chunk, 0.25, k_t, v_t, x_out=x, yhat_out=y)
+    torch.cuda.synchronize()
+    x2 = pk.proxykv_score(ctx, q, kc, kr, case.chunk)
+    y2 = pk.proxykv_map(ctx, x2)
+    idx2 = pk.proxykv_topk(ctx, y2.view(-1, case.N), K).view(case.L_l, case.H_l, K)
+    k2, v2 = pk.proxykv_compact(ctx, k_t, v_t, idx2)
+    torch.cuda.synchronize()
+    assert K == 175
+    assert torch.equal(x, x2) and torch.equal(y, y2) and torch.equal(idx, idx2)
+    assert torch.equal(k_out.view(torch.int16), k2.view(torch.int16)) and torch.equal(v_out.view(torch.int16), v2.view(torch.int16))
+    assert_close(x, oracle.score(q.double().cpu(), kc.double().cpu(), kr.double().cpu(), case.chunk, reduce="sum"), "prune sum x")
+    pk.proxykv_destroy(ctx)
