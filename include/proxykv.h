@@ -141,7 +141,10 @@ int proxykv_score_self(proxykv_ctx* ctx, const void* q, const void* k, int32_t d
  * [stride*k, min(stride*k + win, N)), outputs averaged where windows overlap; stage 3: per-token
  * attention of the H_l learned queries over H_kv projected slots, then a linear map to one logit.
  * Matrix products take IEEE half (fp16) operands and accumulate in fp32; the rest is fp32.
- * Needs proxykv_set_mapper_weights (ESTATE otherwise). */
+ * Needs proxykv_set_mapper_weights (ESTATE otherwise).
+ * Distinct proxy layers run side by side on up to four streams that the context owns (default priority); they start
+ * behind the work already queued on `stream` and are joined into it by events before the call returns, so for the
+ * caller everything is ordered on `stream` as for the other entry points. */
 int proxykv_map(proxykv_ctx* ctx, const float* x, int64_t N, float* yhat, void* stream);
 
 /* Per-row Top-K (Sec. 3: mask M by Top-K thresholding of the mapped scores; Sec. 4.3).

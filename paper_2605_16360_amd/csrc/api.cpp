@@ -78,7 +78,8 @@ int ensure(proxykv_ctx* ctx, DeviceBuffer& b, size_t bytes, hipStream_t stream) 
 
 struct Sizes {
   size_t neg_lse, x_ws, yhat_ws, h1, z_local, x, xb, qk, vt, ao, tmp, hid, zg, kv3;
-  size_t total() const { return neg_lse + x_ws + yhat_ws + h1 + z_local + x + xb + qk + vt + ao + tmp + hid + zg + kv3; }
+  size_t mapper() const { return h1 + z_local + x + xb + qk + vt + ao + tmp + hid + zg + kv3; }  // one lane's activations
+  size_t total() const { return neg_lse + x_ws + yhat_ws + mapper(); }
 };
 
 Sizes workspace_sizes(const proxykv_config& c, int64_t N, int64_t N_q) {
@@ -114,7 +115,19 @@ int reserve_all(proxykv_ctx* ctx, int64_t N, int64_t N_q, bool score_part, bool 
     if ((rc = ensure(ctx, ctx->yhat_ws, s.yhat_ws, stream))) return rc;
   }
   if (map_part) {
-    pkv::MapperWorkspace& m = ctx->m;
+    int64_t n_win, T;
+    pkv::window_plan(N, ctx->cfg.win, ctx->cfg.stride, &n_win, &T);
+    const int lanes = pkv::map_lanes(T, ctx->distinct_layers);
+    if (lanes > 1 && !ctx->lanes_created) {
+      for (int i = 1; i < pkv::kMapLanes; ++i) {
+        PKV_HIP(ctx, hipStreamCreateWithFlags(&ctx->lane_stream[i], hipStreamNonBlocking));
+        PKV_HIP(ctx, hipEventCreateWithFlags(&ctx->lane_join[i], hipEventDisableTiming));
+      }
+      PKV_HIP(ctx, hipEventCreateWithFlags(&ctx->lane_fork, hipEventDisableTiming));
+      ctx->lanes_created = true;
+    }
+   for (int lane = 0; lane < lanes; ++lane) {
+    pkv::MapperWorkspace& m = ctx->m[lane];
     if ((rc = ensure(ctx, m.h1, s.h1, stream))) return rc;
     if ((rc = ensure(ctx, m.z_local, s.z_local, stream))) return rc;
     if ((rc = ensure(ctx, m.x, s.x, stream))) return rc;
@@ -126,6 +139,7 @@ int reserve_all(proxykv_ctx* ctx, int64_t N, int64_t N_q, bool score_part, bool 
     if ((rc = ensure(ctx, m.hid, s.hid, stream))) return rc;
     if ((rc = ensure(ctx, m.zg, s.zg, stream))) return rc;
     if ((rc = ensure(ctx, m.kv3, s.kv3, stream))) return rc;
+   }
   }
   return rc;
 }
@@ -277,17 +291,19 @@ int proxykv_create(proxykv_ctx** out, const proxykv_config* cfg) {
   ctx->pairing.resize(cfg->L_l);
   for (int ll = 0; ll < cfg->L_l; ++ll)
     ctx->pairing[ll] = (int32_t)(((int64_t)(ll + 1) * cfg->L_s + cfg->L_l - 1) / cfg->L_l - 1);
+  ctx->distinct_layers = 0;
+  for (int ll = 0; ll < cfg->L_l; ++ll) ctx->distinct_layers += (ll == 0 || ctx->pairing[ll] != ctx->pairing[ll - 1]);
   *out = ctx;
   return PROXYKV_OK;
 }
 
 int proxykv_destroy(proxykv_ctx* ctx) {
   if (!ctx) return PROXYKV_OK;
-  DeviceBuffer* all[] = {&ctx->weight_blob, &ctx->q_bf16, &ctx->kctx_bf16, &ctx->krec_bf16, &ctx->neg_lse,
-                         &ctx->x_ws,        &ctx->yhat_ws, &ctx->m.h1,     &ctx->m.z_local, &ctx->m.x,
-                         &ctx->m.xb,        &ctx->m.qk,    &ctx->m.vt,     &ctx->m.ao,      &ctx->m.tmp,
-                         &ctx->m.hid,       &ctx->m.zg,    &ctx->m.kv3};
-  bool any = ctx->ev_created;
+  std::vector<DeviceBuffer*> all = {&ctx->weight_blob, &ctx->q_bf16, &ctx->kctx_bf16, &ctx->krec_bf16,
+                                    &ctx->neg_lse,     &ctx->x_ws,   &ctx->yhat_ws};
+  for (pkv::MapperWorkspace& m : ctx->m)
+    for (DeviceBuffer* b : {&m.h1, &m.z_local, &m.x, &m.xb, &m.qk, &m.vt, &m.ao, &m.tmp, &m.hid, &m.zg, &m.kv3}) all.push_back(b);
+  bool any = ctx->ev_created || ctx->lanes_created;
   for (DeviceBuffer* b : all) any = any || b->ptr;
   if (any) {
     (void)hipSetDevice(ctx->cfg.device);
@@ -295,6 +311,13 @@ int proxykv_destroy(proxykv_ctx* ctx) {
     for (DeviceBuffer* b : all) free_buffer(*b);
     if (ctx->ev_created)
       for (int i = 0; i < PROXYKV_N_STAGES + 1; ++i) (void)hipEventDestroy(ctx->ev[i]);
+    if (ctx->lanes_created) {
+      for (int i = 1; i < pkv::kMapLanes; ++i) {
+        if (ctx->lane_stream[i]) (void)hipStreamDestroy(ctx->lane_stream[i]);
+        if (ctx->lane_join[i]) (void)hipEventDestroy(ctx->lane_join[i]);
+      }
+      if (ctx->lane_fork) (void)hipEventDestroy(ctx->lane_fork);
+    }
   }
   delete ctx;
   return PROXYKV_OK;
@@ -431,7 +454,16 @@ int proxykv_workspace_bytes(const proxykv_config* cfg, int64_t N, int64_t N_q, s
   int rc = validate_config(cfg);
   if (rc) return rc;
   if ((rc = validate_lengths(N, N_q, 1))) return rc;
-  *out_bytes = workspace_sizes(*cfg, N, N_q).total();
+  const Sizes s = workspace_sizes(*cfg, N, N_q);
+  int64_t n_win, T;
+  pkv::window_plan(N, cfg->win, cfg->stride, &n_win, &T);
+  int distinct = 0, prev = -1;
+  for (int ll = 0; ll < cfg->L_l; ++ll) {
+    const int ls = (int)(((int64_t)(ll + 1) * cfg->L_s + cfg->L_l - 1) / cfg->L_l - 1);
+    distinct += ls != prev;
+    prev = ls;
+  }
+  *out_bytes = s.total() + (size_t)(pkv::map_lanes(T, distinct) - 1) * s.mapper();
   return PROXYKV_OK;
 }
 

@@ -700,13 +700,13 @@ hipError_t launch_gemm(const uint16_t* A, int lda, const uint16_t* W, int64_t M,
 
 }  // namespace
 
-hipError_t mapper_forward(proxykv_ctx* ctx, const float* x_in, int64_t N, float* yhat, hipStream_t stream) {
+namespace {
+
+// The network for one proxy layer (input rows xl [H_kv, N]); writes yhat rows of the target layers ll .. ll_hi - 1.
+hipError_t mapper_layer(proxykv_ctx* ctx, MapperWorkspace& m, const float* xl, int64_t N, float* yhat, int ll, int ll_hi,
+                        int n_cu, hipStream_t stream) {
   const proxykv_config& c = ctx->cfg;
   const MapperWeights& w = ctx->w;
-  MapperWorkspace& m = ctx->m;
-  int n_cu = 0, dev = 0;
-  PKV_TRY(hipGetDevice(&dev));
-  PKV_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
   int64_t n_win, T;
   window_plan(N, c.win, c.stride, &n_win, &T);
   uint16_t* h1 = (uint16_t*)m.h1.ptr;
@@ -723,54 +723,78 @@ hipError_t mapper_forward(proxykv_ctx* ctx, const float* x_in, int64_t N, float*
   const unsigned ew_blocks_T = (unsigned)((T * (kDT / 4) + 255) / 256);
   const unsigned ew_blocks_N = (unsigned)((N * (kDT / 4) + 255) / 256);
 
-  int ll = 0;
+  // stage 1
+  stem_conv1_kernel<<<(unsigned)((N + kStemTok - 1) / kStemTok), 256, 0, stream>>>(xl, w.conv1_w, w.bn1_scale, w.bn1_shift, h1,
+                                                                                  c.H_kv, (int)N, c.c_mid);
+  PKV_TRY(hipGetLastError());
+  EpiArgs e2 = {w.bn2_scale, w.bn2_shift, z_local, nullptr};
+  PKV_TRY(launch_gemm<kEpiAffineGeluF32>(h1, c.c_mid, w.conv2_w, N, kDT, 3 * c.c_mid, e2, n_cu, stream));
+
+  // stage 2
+  gather_pe_kernel<<<ew_blocks_T, 256, 0, stream>>>(z_local, w.pe, x, xb, T);
+  PKV_TRY(hipGetLastError());
+  for (int li = 0; li < c.n_enc_layers; ++li) {
+    const EncoderLayerWeights& e = w.enc[li];
+    EpiArgs eq = {e.in_b, nullptr, nullptr, qk};
+    PKV_TRY(launch_gemm<kEpiBiasH>(xb, kDT, e.in_w, T, 3 * kDT, kDT, eq, n_cu, stream));
+    v_transpose_kernel<<<dim3(kWin / 64, kHeads, (unsigned)n_win), 256, 0, stream>>>(qk, vt, T);
+    PKV_TRY(hipGetLastError());
+    window_attention_kernel<<<(unsigned)(n_win * kHeads * (kWin / 256)), 256, 0, stream>>>(qk, vt, ao, T, (int)n_win);
+    PKV_TRY(hipGetLastError());
+    EpiArgs eo = {e.out_b, nullptr, tmp, nullptr};
+    PKV_TRY(launch_gemm<kEpiBiasF32>(ao, kDT, e.out_w, T, kDT, kDT, eo, n_cu, stream));
+    layernorm_kernel<<<(unsigned)((T + 3) / 4), 256, 0, stream>>>(tmp, e.ln1_g, e.ln1_b, x, xb, T);
+    PKV_TRY(hipGetLastError());
+    EpiArgs e1 = {e.ffn1_b, nullptr, nullptr, hid};
+    PKV_TRY(launch_gemm<kEpiBiasReluH>(xb, kDT, e.ffn1_w, T, c.d_ffn, kDT, e1, n_cu, stream));
+    EpiArgs ef = {e.ffn2_b, nullptr, tmp, nullptr};
+    PKV_TRY(launch_gemm<kEpiBiasF32>(hid, c.d_ffn, e.ffn2_w, T, kDT, c.d_ffn, ef, n_cu, stream));
+    layernorm_kernel<<<(unsigned)((T + 3) / 4), 256, 0, stream>>>(tmp, e.ln2_g, e.ln2_b, x, xb, T);
+    PKV_TRY(hipGetLastError());
+  }
+  overlap_avg_kernel<<<ew_blocks_N, 256, 0, stream>>>(x, zg, N, (int)n_win);
+  PKV_TRY(hipGetLastError());
+
+  // stage 3
+  const int nkv = kv3_stride(c);
+  EpiArgs e3 = {w.kv_b, nullptr, kv3, nullptr};
+  PKV_TRY(launch_gemm<kEpiBiasF32>(zg, kDT, w.kv_w, N, nkv, kDT, e3, n_cu, stream));
+  const int tok_per_block = 256 / c.H_l;
+  stage3_kernel<<<(unsigned)((N + tok_per_block - 1) / tok_per_block), 256, 0, stream>>>(kv3, w.queries, w.out_w, w.out_b, yhat, N,
+                                                                                        c.H_kv, c.H_l, nkv, ll, ll_hi);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t mapper_forward(proxykv_ctx* ctx, const float* x_in, int64_t N, float* yhat, hipStream_t stream) {
+  const proxykv_config& c = ctx->cfg;
+  int n_cu = 0, dev = 0;
+  PKV_TRY(hipGetDevice(&dev));
+  PKV_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+  int64_t n_win, T;
+  window_plan(N, c.win, c.stride, &n_win, &T);
+  // distinct proxy layers are dealt round-robin to the lanes; lane 0 is the caller's stream, the others start behind
+  // the work already queued there and are joined into it at the end
+  const int lanes = map_lanes(T, ctx->distinct_layers);
+  if (lanes > 1) {
+    PKV_TRY(hipEventRecord(ctx->lane_fork, stream));
+    for (int lane = 1; lane < lanes; ++lane) PKV_TRY(hipStreamWaitEvent(ctx->lane_stream[lane], ctx->lane_fork, 0));
+  }
+  int ll = 0, item = 0;
   while (ll < c.L_l) {
     const int ls = ctx->pairing[ll];
     int ll_hi = ll + 1;
     while (ll_hi < c.L_l && ctx->pairing[ll_hi] == ls) ++ll_hi;
-    const float* xl = x_in + (size_t)ls * c.H_kv * N;
-
-    // stage 1
-    stem_conv1_kernel<<<(unsigned)((N + kStemTok - 1) / kStemTok), 256, 0, stream>>>(xl, w.conv1_w, w.bn1_scale, w.bn1_shift,
-                                                                                    h1, c.H_kv, (int)N, c.c_mid);
-    PKV_TRY(hipGetLastError());
-    EpiArgs e2 = {w.bn2_scale, w.bn2_shift, z_local, nullptr};
-    PKV_TRY(launch_gemm<kEpiAffineGeluF32>(h1, c.c_mid, w.conv2_w, N, kDT, 3 * c.c_mid, e2, n_cu, stream));
-
-    // stage 2
-    gather_pe_kernel<<<ew_blocks_T, 256, 0, stream>>>(z_local, w.pe, x, xb, T);
-    PKV_TRY(hipGetLastError());
-    for (int li = 0; li < c.n_enc_layers; ++li) {
-      const EncoderLayerWeights& e = w.enc[li];
-      EpiArgs eq = {e.in_b, nullptr, nullptr, qk};
-      PKV_TRY(launch_gemm<kEpiBiasH>(xb, kDT, e.in_w, T, 3 * kDT, kDT, eq, n_cu, stream));
-      v_transpose_kernel<<<dim3(kWin / 64, kHeads, (unsigned)n_win), 256, 0, stream>>>(qk, vt, T);
-      PKV_TRY(hipGetLastError());
-      window_attention_kernel<<<(unsigned)(n_win * kHeads * (kWin / 256)), 256, 0, stream>>>(qk, vt, ao, T, (int)n_win);
-      PKV_TRY(hipGetLastError());
-      EpiArgs eo = {e.out_b, nullptr, tmp, nullptr};
-      PKV_TRY(launch_gemm<kEpiBiasF32>(ao, kDT, e.out_w, T, kDT, kDT, eo, n_cu, stream));
-      layernorm_kernel<<<(unsigned)((T + 3) / 4), 256, 0, stream>>>(tmp, e.ln1_g, e.ln1_b, x, xb, T);
-      PKV_TRY(hipGetLastError());
-      EpiArgs e1 = {e.ffn1_b, nullptr, nullptr, hid};
-      PKV_TRY(launch_gemm<kEpiBiasReluH>(xb, kDT, e.ffn1_w, T, c.d_ffn, kDT, e1, n_cu, stream));
-      EpiArgs ef = {e.ffn2_b, nullptr, tmp, nullptr};
-      PKV_TRY(launch_gemm<kEpiBiasF32>(hid, c.d_ffn, e.ffn2_w, T, kDT, c.d_ffn, ef, n_cu, stream));
-      layernorm_kernel<<<(unsigned)((T + 3) / 4), 256, 0, stream>>>(tmp, e.ln2_g, e.ln2_b, x, xb, T);
-      PKV_TRY(hipGetLastError());
-    }
-    overlap_avg_kernel<<<ew_blocks_N, 256, 0, stream>>>(x, zg, N, (int)n_win);
-    PKV_TRY(hipGetLastError());
-
-    // stage 3
-    const int nkv = kv3_stride(c);
-    EpiArgs e3 = {w.kv_b, nullptr, kv3, nullptr};
-    PKV_TRY(launch_gemm<kEpiBiasF32>(zg, kDT, w.kv_w, N, nkv, kDT, e3, n_cu, stream));
-    const int tok_per_block = 256 / c.H_l;
-    stage3_kernel<<<(unsigned)((N + tok_per_block - 1) / tok_per_block), 256, 0, stream>>>(
-        kv3, w.queries, w.out_w, w.out_b, yhat, N, c.H_kv, c.H_l, nkv, ll, ll_hi);
-    PKV_TRY(hipGetLastError());
+    const int lane = item % lanes;
+    PKV_TRY(mapper_layer(ctx, ctx->m[lane], x_in + (size_t)ls * c.H_kv * N, N, yhat, ll, ll_hi, n_cu,
+                         lane == 0 ? stream : ctx->lane_stream[lane]));
     ll = ll_hi;
+    ++item;
+  }
+  for (int lane = 1; lane < lanes; ++lane) {
+    PKV_TRY(hipEventRecord(ctx->lane_join[lane], ctx->lane_stream[lane]));
+    PKV_TRY(hipStreamWaitEvent(stream, ctx->lane_join[lane], 0));
   }
   return hipSuccess;
 }
