@@ -278,6 +278,27 @@ def test_mapper_matches_oracle(name):
                 assert torch.equal(y[a], y[b])
 
 
+def test_mapper_context_reuse_across_lengths():
+    """One context called with a short, a longer and again a shorter sequence (the workspace of every lane grows in
+    between; three distinct proxy layers run side by side): same bits as a fresh context each time, and the oracle's
+    values on the last one."""
+    case = synth.scaled_case(synth.CASES["llama_8k"], name="reuse", L_s=3, H_kv=2, H_q=2, L_l=3, H_l=4, N=700, N_q=64, chunk=64,
+                             n_planted=0)
+    w = synth.make_mapper_weights(case.H_kv, case.H_l)
+    g = torch.Generator().manual_seed(23)
+    ctx = _ctx(case, w)
+    for N in (700, 2300, 300):
+        X = (torch.rand(case.L_s, case.H_kv, N, generator=g) ** 8).to(torch.float32)
+        y = pk.proxykv_map(ctx, X.cuda())
+        fresh = _ctx(case, w)
+        y_fresh = pk.proxykv_map(fresh, X.cuda())
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_fresh), N
+        pk.proxykv_destroy(fresh)
+    assert_close(y, oracle.mapper(X, w, case.L_l), "map after reuse, N=300")
+    pk.proxykv_destroy(ctx)
+
+
 # ----------------------------------------------------------------------------------------------
 # whole path
 # ----------------------------------------------------------------------------------------------
