@@ -261,6 +261,16 @@ def test_llama_8k_score_self_full_size():
     pk.proxykv_destroy(ctx)
 
 
+@pytest.mark.parametrize("name,keep_ratio", [("llama_32k", 0.1), ("llama_32k", 0.5), ("qwen32b_32k", 0.9)])
+def test_selection_and_compaction_at_the_other_keep_ratios(name, keep_ratio):
+    """Top-K on every row, both compactions, the mask and the pooled budget at the workloads' other retention ratios."""
+    case = synth.CASES[name]
+    ctx = pk.proxykv_create(pk.config_for_case(case))
+    k_t, v_t = _check_topk_compact(case, ctx, keep_ratio)
+    del k_t, v_t
+    pk.proxykv_destroy(ctx)
+
+
 def test_llama_32k_full_size():
     """The workload bench.py times."""
     N = synth.CASES["llama_32k"].N
