@@ -355,13 +355,13 @@ hipError_t launch_score_colmax(const uint16_t* q, const uint16_t* k_ctx, const f
     constexpr int NCOL = 4;
     const unsigned grid = group_grid((int64_t)L_s * H_kv, (N + 128 * NCOL - 1) / (128 * NCOL));
     if (grid == 0) return hipErrorInvalidValue;
-  if (grid == 0) return hipErrorInvalidValue;
     score_colmax_kernel<64, NCOL><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, L_s, H_q, G, (int)N, (int)N_q, c);
   } else {
-    constexpr int NCOL = 2;
+    // one workgroup per CU (the resident keys of 4 column sub-tiles alone take 128 registers): a wave has the SIMD's
+    // whole register file, and the pinned issue order keeps the matrix pipe fed without a second wave
+    constexpr int NCOL = 4;
     const unsigned grid = group_grid((int64_t)L_s * H_kv, (N + 128 * NCOL - 1) / (128 * NCOL));
     if (grid == 0) return hipErrorInvalidValue;
-  if (grid == 0) return hipErrorInvalidValue;
     score_colmax_kernel<128, NCOL><<<grid, 256, 0, stream>>>(q, k_ctx, neg_lse, x, L_s, H_q, G, (int)N, (int)N_q, c);
   }
   return hipGetLastError();
