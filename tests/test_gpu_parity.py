@@ -278,6 +278,21 @@ def test_mapper_matches_oracle(name):
                 assert torch.equal(y[a], y[b])
 
 
+@pytest.mark.parametrize("N", [1, 2, 65, 2049])
+def test_mapper_degenerate_lengths(N):
+    """One token, two tokens, just over one MFMA key tile, and one token past the first window (a second window of 1025)."""
+    case = synth.scaled_case(synth.CASES["llama_8k"], name=f"len{N}", L_s=2, H_kv=2, H_q=2, L_l=2, H_l=4, N=N, N_q=1, chunk=1,
+                             n_planted=0)
+    w = synth.make_mapper_weights(case.H_kv, case.H_l)
+    g = torch.Generator().manual_seed(100 + N)
+    X = (torch.rand(case.L_s, case.H_kv, N, generator=g) ** 8).to(torch.float32)
+    ctx = _ctx(case, w)
+    y = pk.proxykv_map(ctx, X.cuda())
+    torch.cuda.synchronize()
+    assert_close(y, oracle.mapper(X, w, case.L_l), f"map N={N}")
+    pk.proxykv_destroy(ctx)
+
+
 def test_mapper_context_reuse_across_lengths():
     """One context called with a short, a longer and again a shorter sequence (the workspace of every lane grows in
     between; three distinct proxy layers run side by side): same bits as a fresh context each time, and the oracle's
