@@ -219,6 +219,22 @@ def test_score_self_fp32_inputs_and_block_boundaries():
         assert_close(x, ref, f"score_self fp32 N={N}")
 
 
+@pytest.mark.parametrize("N,N_q,chunk", [(1, 1, 1), (1, 300, 100), (129, 1, 5), (2, 130, 1000), (513, 257, 256)])
+def test_score_degenerate_shapes(N, N_q, chunk):
+    """One context key, one query, a chunk longer than the query axis, lengths one past the tile sizes; max and sum forms."""
+    case = synth.scaled_case(synth.CASES["llama_8k"], name=f"deg_{N}_{N_q}", L_s=1, H_q=4, H_kv=2, d=64, L_l=1, H_l=2, N=N, N_q=N_q,
+                             chunk=chunk, n_planted=0)
+    q, kc, kr = synth.make_proxy_qk(case)
+    for reduce, code in (("max", pk.PROXYKV_REDUCE_MAX), ("sum", pk.PROXYKV_REDUCE_SUM)):
+        cfg = pk.config_for_case(case)
+        cfg.reduce = code
+        ctx = pk.proxykv_create(cfg)
+        x = pk.proxykv_score(ctx, q.cuda(), kc.cuda(), kr.cuda(), chunk)
+        torch.cuda.synchronize()
+        assert_close(x, oracle.score(q.double(), kc.double(), kr.double(), chunk, reduce=reduce), f"score {reduce} N={N} N_q={N_q}")
+        pk.proxykv_destroy(ctx)
+
+
 def test_score_tiny_case_fp32_inputs_and_planted_keys():
     case = synth.CASES["tiny"]
     q, kc, kr = synth.make_proxy_qk(case)
