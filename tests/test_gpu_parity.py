@@ -235,6 +235,26 @@ def test_score_degenerate_shapes(N, N_q, chunk):
         pk.proxykv_destroy(ctx)
 
 
+@pytest.mark.parametrize("scale", [8.0, 30.0])
+def test_score_large_logits(scale):
+    """Inputs scaled up until the softmax rows are nearly one-hot (logits of several hundred): the running reference of
+    pass 1 is replaced many times, probabilities are either about one or far below the absolute tolerance."""
+    case = _score_case("d64_ragged")
+    q, kc, kr = synth.make_proxy_qk(case)
+    q, kc, kr = (q.float() * scale).to(torch.bfloat16), (kc.float() * scale).to(torch.bfloat16), (kr.float() * scale).to(torch.bfloat16)
+    for reduce, code in (("max", pk.PROXYKV_REDUCE_MAX), ("sum", pk.PROXYKV_REDUCE_SUM)):
+        cfg = pk.config_for_case(case)
+        cfg.reduce = code
+        ctx = pk.proxykv_create(cfg)
+        x = pk.proxykv_score(ctx, q.cuda(), kc.cuda(), kr.cuda(), case.chunk)
+        torch.cuda.synchronize()
+        assert_close(x, oracle.score(q.double(), kc.double(), kr.double(), case.chunk, reduce=reduce), f"score {reduce} x{scale}")
+        pk.proxykv_destroy(ctx)
+    xs = pk.proxykv_score_self(_ctx(case), q.cuda(), kr.cuda())
+    torch.cuda.synchronize()
+    assert_close(xs, oracle.score_self(q.double(), kr.double()), f"score_self x{scale}")
+
+
 def test_score_tiny_case_fp32_inputs_and_planted_keys():
     case = synth.CASES["tiny"]
     q, kc, kr = synth.make_proxy_qk(case)
