@@ -7,6 +7,7 @@ The oracle shares no code with the HIP library.
 from .proxykv_oracle import (  # noqa: F401
     round_bf16,
     round_f16,
+    round_sig11,
     keep_count,
     layer_pairing,
     window_spans,

@@ -58,10 +58,20 @@ def round_f16(x: torch.Tensor) -> torch.Tensor:
     return x.to(torch.float32).to(torch.float16).to(F64)
 
 
+def round_sig11(x: torch.Tensor) -> torch.Tensor:
+    """Round to the nearest value with an 11-bit significand (ties to even) and no
+    limit on the exponent: IEEE half's precision without its range.  Equal to
+    `round_f16` for magnitudes in half's normal range [2^-14, 65520)."""
+    m, e = torch.frexp(x.to(F64))                      # x = m * 2^e with 0.5 <= |m| < 1
+    return torch.ldexp(torch.round(m * 2048.0) / 2048.0, e)
+
+
 def _maybe_round(x: torch.Tensor, on: bool, fmt: str = "f16") -> torch.Tensor:
     if not on:
         return x.to(F64)
-    return round_bf16(x) if fmt == "bf16" else round_f16(x)
+    if fmt == "bf16":
+        return round_bf16(x)
+    return round_sig11(x) if fmt == "sig11" else round_f16(x)
 
 
 def keep_count(N: int, keep_ratio: float) -> int:
@@ -275,12 +285,17 @@ def stem(U: torch.Tensor, w: Weights, round_operands: bool = True) -> torch.Tens
     BatchNorm in inference mode with stored statistics, eps 1e-5; GELU in its
     exact erf form; the convolution runs once over the whole sequence.  The
     first convolution works on the raw fp32 scores; the second one is a matrix
-    product and takes half-precision operands.
+    product and takes half-precision operands.  The feature of Sec. 3 in its
+    sum form is not bounded by one (an attention sink collects a share of every
+    query row, up to G * N_q in total), so the first block's output can leave
+    half's exponent range; what the reading fixes for this operand is its
+    precision (an 11-bit significand), not its range: an implementation holds it
+    as a half value times a power of two of its choosing.
     """
     U = U.to(F64)
     a1 = _conv1d_k3(U, w["stem.conv1.weight"], w["stem.conv1.bias"])
     h1 = _gelu(_batchnorm_eval(a1, w, "stem.bn1"))
-    h1 = _maybe_round(h1, round_operands)
+    h1 = _maybe_round(h1, round_operands, "sig11")
     w2 = _maybe_round(w["stem.conv2.weight"], round_operands)
     a2 = _conv1d_k3(h1, w2, w["stem.conv2.bias"])
     z = _gelu(_batchnorm_eval(a2, w, "stem.bn2"))
@@ -315,7 +330,8 @@ def encoder_layer(x: torch.Tensor, w: Weights, i: int, n_heads: int = 8,
 
     Operand rounding: the inputs of the four linear maps, the q/k/v fed to the
     attention products and the (unnormalised, row-max-shifted) probabilities
-    fed to the P V product are bf16; everything else is wide.
+    fed to the P V product are IEEE half values (see the module docstring);
+    everything else is wide.
     """
     p = f"enc.{i}."
     T, D = x.shape

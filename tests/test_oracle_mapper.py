@@ -180,3 +180,95 @@ def test_parameter_budget_order_of_magnitude():
     assert 0.5 * budget["encoder"] < enc < 2 * budget["encoder"]
     assert 0.25 * budget["head"] < head < 2 * budget["head"]
     assert abs(enc - 18.9) < 0.1          # 6 * (4*512^2 + 2*512*2048 + biases and norms)
+
+
+# ----------------------------------------------------------------------------------------------
+# Operand precision of the mapper (the paper does not state it): why the oracle rounds matrix-product
+# operands to IEEE half and not to bf16.
+# ----------------------------------------------------------------------------------------------
+
+def _encoder_layer_rewritten(x, w, i, rt, n_heads=8, blk=64, lazy=8.0):
+    """The encoder layer of Sec. 4.1 (stage 2) written a second time, as an accelerator would run it: fp32
+    accumulation everywhere, the attention as an online softmax over key blocks whose reference only moves
+    when a logit exceeds it by 2^lazy (probabilities rounded relative to that reference, divided by the
+    unrounded sum afterwards), torch's own layer norm.  Operands of the matrix products are rounded to `rt`
+    at the same places as in oracle.encoder_layer."""
+    f32 = torch.float32
+    r = lambda t: t.to(f32).to(rt).to(f32)
+    p = f"enc.{i}."
+    T, D = x.shape
+    dh = D // n_heads
+    x = x.to(f32)
+    qkv = r(r(x) @ r(w[p + "in_proj.weight"]).T + w[p + "in_proj.bias"])
+    q, k, v = qkv[:, :D], qkv[:, D:2 * D], qkv[:, 2 * D:]
+    c = math.log2(math.e) / math.sqrt(dh)
+    heads = []
+    for h in range(n_heads):
+        qh, kh, vh = (t[:, h * dh:(h + 1) * dh] for t in (q, k, v))
+        m = torch.full((T, 1), -1e30, dtype=f32)
+        l = torch.zeros(T, 1, dtype=f32)
+        o = torch.zeros(T, dh, dtype=f32)
+        for j0 in range(0, T, blk):
+            s = (qh @ kh[j0:j0 + blk].T) * c
+            tm = s.max(dim=1, keepdim=True).values
+            nm = torch.where(tm > m + lazy, tm, m)
+            alpha = torch.exp2(m - nm)
+            l, o, m = l * alpha, o * alpha, nm
+            pt = torch.exp2(s - m)
+            l = l + pt.sum(dim=1, keepdim=True)
+            o = o + r(pt) @ vh[j0:j0 + blk]
+        heads.append(o / l)
+    o = r(torch.cat(heads, dim=1))
+    ln = lambda t, g, b: torch.nn.functional.layer_norm(t, (D,), g, b, 1e-5)
+    x = ln(x + o @ r(w[p + "out_proj.weight"]).T + w[p + "out_proj.bias"], w[p + "ln1.gamma"], w[p + "ln1.beta"])
+    hdn = torch.relu(r(x) @ r(w[p + "ffn1.weight"]).T + w[p + "ffn1.bias"])
+    y2 = r(hdn) @ r(w[p + "ffn2.weight"]).T + w[p + "ffn2.bias"]
+    return ln(x + y2, w[p + "ln2.gamma"], w[p + "ln2.beta"])
+
+
+def test_two_correct_evaluations_agree_under_half_operands_but_not_under_bf16(monkeypatch):
+    """Two evaluations of the same mapper that differ only in what no reading of the paper fixes (fp64 against
+    fp32 accumulation, plain against online softmax) and round the matrix-product operands at the same places.
+    With bf16 operands their outputs drift apart by more than the absolute tolerance asked of the mapped scores
+    (2e-3): activations are re-rounded about thirty times on the way through the six layers, values that differ in
+    the last bit round differently, and the difference grows to the size of bf16's rounding step.  With IEEE half
+    operands (11-bit significand, same matrix-core rate) the same two evaluations stay below a quarter of it.
+    This is the ground for the oracle's half-precision reading; the library follows it."""
+    import oracle.proxykv_oracle as O
+    H_s, H_l, N = 8, 64, 1024
+    w = synth.make_mapper_weights(H_s, H_l)
+    worst = {}
+    for name, rt in (("bf16", torch.bfloat16), ("f16", torch.float16)):
+        monkeypatch.setattr(O, "_maybe_round", lambda x, on, fmt="f16", rt=rt: x.to(torch.float32).to(rt).to(O.F64) if on else x.to(O.F64))
+        worst[name] = []
+        for seed in (0, 1):
+            g = torch.Generator().manual_seed(7 * N + seed)
+            X = (torch.rand(H_s, N, generator=g) ** 8).to(torch.float32)
+            a = O.mapper_layer(X, w)
+            with monkeypatch.context() as mp:
+                mp.setattr(O, "encoder_layer", lambda x, w_, i, n_heads=8, round_operands=True, rt=rt:
+                           _encoder_layer_rewritten(x, w_, i, rt, n_heads).double())
+                b = O.mapper_layer(X, w)
+            err = (a - b).abs()
+            worst[name].append((float(err.max()), float((err / (2e-3 + 1e-2 * a.abs())).max())))
+    assert all(e > 2e-3 for e, _ in worst["bf16"]), worst
+    assert all(r > 0.5 for _, r in worst["bf16"]), worst          # most of the allclose bound is gone too
+    assert all(e < 5e-4 and r < 0.25 for e, r in worst["f16"]), worst
+
+
+def test_round_sig11_is_half_precision_without_the_range():
+    """The rounding of the second convolution's operand: IEEE half's values where half has them, the same
+    relative spacing beyond its range (every power-of-two multiple of a representable value is representable)."""
+    g = torch.Generator().manual_seed(3)
+    x = torch.randn(20000, dtype=torch.float64, generator=g) * torch.pow(2.0, torch.randint(-13, 15, (20000,), generator=g).double())
+    x = x[(x.abs() >= 2.0 ** -14) & (x.abs() < 65504.0)]
+    assert torch.equal(oracle.round_sig11(x), oracle.round_f16(x))
+    for k in (-40, -17, 5, 30):
+        assert torch.equal(oracle.round_sig11(x * 2.0 ** k), oracle.round_sig11(x) * 2.0 ** k)
+    big = torch.tensor([65504.0, 65519.9, 65520.0, 1.0e5, 3.0e5 + 7.0, 1.2e6, -2.5e9], dtype=torch.float64)
+    r = oracle.round_sig11(big)
+    assert bool(torch.isfinite(r).all()) and bool(((r - big).abs() <= big.abs() * 2.0 ** -11).all())
+    assert float(r[0]) == 65504.0 and float(r[2]) == 65536.0            # ties to even: 65520 lies halfway between 65504 and 65536
+    # hand values: 11 significant bits around 1 are multiples of 2^-10, ties go to the even neighbour
+    hand = torch.tensor([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -10 + 2.0 ** -12, 0.0, -3.0], dtype=torch.float64)
+    assert oracle.round_sig11(hand).tolist() == [1.0, 1.0 + 2.0 ** -9, 1.0 + 2.0 ** -10, 0.0, -3.0]
