@@ -45,7 +45,8 @@ typedef enum {
   PROXYKV_EUNSUPPORTED = -2, /* a shape or switch this build has no kernel for */
   PROXYKV_ENOMEM = -3,       /* device allocation failed */
   PROXYKV_ESTATE = -4,       /* mapper weights not set, context destroyed, ... */
-  PROXYKV_EHIP = -5          /* a HIP runtime call failed */
+  PROXYKV_EHIP = -5,         /* a HIP runtime call failed */
+  PROXYKV_ELIMIT = -6        /* a size beyond the fixed limit that the entry point documents */
 } proxykv_status;
 
 typedef enum { PROXYKV_BF16 = 0, PROXYKV_FP32 = 1 } proxykv_dtype;
@@ -65,7 +66,8 @@ typedef struct {
    * FFN 4*d_time, window 2048, stride 1024; c_mid (width between the two stem convolutions) and
    * d_head_x (width of the stage-3 head slots) are not given there: 256 and 64 are this build's
    * reading.  This build has kernels for d_time = 512, n_enc_heads = 8 (head width 64),
-   * d_head_x = 64, c_mid and d_ffn multiples of 128, win = 2048, stride = 1024. */
+   * d_head_x = 64, c_mid and d_ffn multiples of 256, win = 2048, stride = 1024, H_kv <= 16,
+   * H_l <= 64 (PROXYKV_EUNSUPPORTED otherwise). */
   int32_t d_time, c_mid, n_enc_layers, n_enc_heads, d_ffn, d_head_x, win, stride;
   int32_t reduce; /* proxykv_reduce */
   int32_t device; /* HIP device ordinal */
@@ -150,7 +152,9 @@ int proxykv_map(proxykv_ctx* ctx, const float* x, int64_t N, float* yhat, void* 
 /* Per-row Top-K (Sec. 3: mask M by Top-K thresholding of the mapped scores; Sec. 4.3).
  *   scores [rows, N] fp32, idx_out [rows, K] int32.
  * Keeps the K entries that come first under the total order (higher score first, equal scores by
- * lower index; -0.0 == +0.0; NaN below every number) and writes their indices in ascending order. */
+ * lower index; -0.0 == +0.0; NaN below every number) and writes their indices in ascending order.
+ * A row of up to 36 864 scores is selected by one workgroup; a longer row is split over several, which meet in
+ * per-row histograms in the context's workspace (then rows <= 65535, PROXYKV_EUNSUPPORTED otherwise). */
 int proxykv_topk(proxykv_ctx* ctx, const float* scores, int64_t rows, int64_t N, int64_t K,
                  int32_t* idx_out, void* stream);
 
@@ -158,7 +162,9 @@ int proxykv_topk(proxykv_ctx* ctx, const float* scores, int64_t rows, int64_t N,
  *   k_out[r, j, :] = k_in[r, idx[r, j], :]   and the same for v.
  *   k_in, v_in [rows, N, D] 16-bit elements; idx [rows, K] int32 in [0, N); k_out, v_out
  *   [rows, K, D].  rows = L_l * H_l.  Outputs must not overlap inputs.  Indices are not checked
- *   on the device: out-of-range indices are the caller's error (proxykv_topk never produces one). */
+ *   on the device: out-of-range indices are the caller's error (proxykv_topk never produces one).
+ *   Limits: rows <= 65535 (PROXYKV_EINVAL); D*2 bytes a multiple of 16, at most 4096, and D*2/16 a divisor of
+ *   256 (PROXYKV_EUNSUPPORTED). */
 int proxykv_compact(proxykv_ctx* ctx, const void* k_in, const void* v_in, const int32_t* idx,
                     int64_t rows, int64_t N, int64_t K, int64_t D, void* k_out, void* v_out,
                     void* stream);
@@ -205,12 +211,18 @@ int proxykv_prune(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const 
                   const void* k_in, const void* v_in, void* k_out, void* v_out, int32_t* idx_out,
                   float* x_out, float* yhat_out, int64_t* K_host, void* stream);
 
+/* Sec. 4.3 names a Top-K kernel that materialises the mask in place.  With this switch on (the default) proxykv_prune
+ * runs selection and gather as ONE launch: the workgroup that has written a stretch of a row's kept indices moves
+ * those tokens' K and V rows itself (stage timing then books the whole launch as the compaction stage).  Off: the
+ * kernels of proxykv_topk and proxykv_compact one after the other.  Same bits either way. */
+int proxykv_set_fused_select(proxykv_ctx* ctx, int on);
+
 /* Stage timing of proxykv_prune, for benchmarks.  With timing switched on, proxykv_prune records a
  * HIP event on its stream at each stage boundary (no synchronisation, no allocation in the call).
  * proxykv_profile_read waits for the last event of the most recent proxykv_prune and writes the
  * PROXYKV_N_STAGES durations in milliseconds to ms_host (HOST array): score pass 1 (row
  * log-sum-exp), score pass 2 (column max), mapper, top-k, compaction.  ESTATE if timing is off or
- * no complete proxykv_prune has been recorded since it was switched on. */
+ * the context's most recent scoring call was not a complete proxykv_prune. */
 #define PROXYKV_N_STAGES 5
 int proxykv_profile_enable(proxykv_ctx* ctx, int on);
 int proxykv_profile_read(proxykv_ctx* ctx, float* ms_host);

@@ -13,7 +13,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libproxykv.so")
 
-PROXYKV_OK, PROXYKV_EINVAL, PROXYKV_EUNSUPPORTED, PROXYKV_ENOMEM, PROXYKV_ESTATE, PROXYKV_EHIP = 0, -1, -2, -3, -4, -5
+PROXYKV_OK, PROXYKV_EINVAL, PROXYKV_EUNSUPPORTED, PROXYKV_ENOMEM, PROXYKV_ESTATE, PROXYKV_EHIP, PROXYKV_ELIMIT = 0, -1, -2, -3, -4, -5, -6
 PROXYKV_BF16, PROXYKV_FP32 = 0, 1
 PROXYKV_REDUCE_MAX, PROXYKV_REDUCE_SUM = 0, 1
 
@@ -21,7 +21,7 @@ EXPORTS = [
     "proxykv_default_mapper", "proxykv_create", "proxykv_destroy", "proxykv_mapper_weight_count",
     "proxykv_set_mapper_weights", "proxykv_workspace_bytes", "proxykv_reserve", "proxykv_keep_count",
     "proxykv_layer_pairing", "proxykv_score", "proxykv_score_self", "proxykv_map", "proxykv_topk", "proxykv_compact", "proxykv_compact_inplace",
-    "proxykv_mask", "proxykv_topk_pooled", "proxykv_compact_pooled", "proxykv_prune",
+    "proxykv_mask", "proxykv_topk_pooled", "proxykv_compact_pooled", "proxykv_prune", "proxykv_set_fused_select",
     "proxykv_profile_enable", "proxykv_profile_read", "proxykv_strerror", "proxykv_last_hip_error",
 ]
 STAGES = ("score_lse", "score_colmax", "map", "topk", "compact")
@@ -76,6 +76,7 @@ def load() -> ctypes.CDLL:
     lib.proxykv_compact_pooled.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, vp]
     lib.proxykv_prune.argtypes = [vp, vp, vp, vp, i32, i64, i64, i32, f64, vp, vp, vp, vp, vp, vp, vp,
                                   ctypes.POINTER(i64), vp]
+    lib.proxykv_set_fused_select.argtypes = [vp, ctypes.c_int]
     lib.proxykv_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.proxykv_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.proxykv_strerror.argtypes = [ctypes.c_int]; lib.proxykv_strerror.restype = ctypes.c_char_p
@@ -191,6 +192,10 @@ def proxykv_layer_pairing(cfg: proxykv_config):
     arr = (ctypes.c_int32 * cfg.L_l)()
     _check(load().proxykv_layer_pairing(ctypes.byref(cfg), arr), "proxykv_layer_pairing")
     return list(arr)
+
+
+def proxykv_set_fused_select(ctx: Context, on: bool) -> None:
+    _check(load().proxykv_set_fused_select(ctx.handle, int(bool(on))), "proxykv_set_fused_select", ctx.handle)
 
 
 def proxykv_profile_enable(ctx: Context, on: bool) -> None:

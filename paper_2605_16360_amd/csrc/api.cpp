@@ -113,6 +113,7 @@ int reserve_all(proxykv_ctx* ctx, int64_t N, int64_t N_q, bool score_part, bool 
   if (prune_part) {
     if ((rc = ensure(ctx, ctx->x_ws, s.x_ws, stream))) return rc;
     if ((rc = ensure(ctx, ctx->yhat_ws, s.yhat_ws, stream))) return rc;
+    if ((rc = ensure(ctx, ctx->topk_ws, pkv::topk_scratch_bytes((int64_t)ctx->cfg.L_l * ctx->cfg.H_l, N), stream))) return rc;
   }
   if (map_part) {
     int64_t n_win, T;
@@ -300,7 +301,7 @@ int proxykv_create(proxykv_ctx** out, const proxykv_config* cfg) {
 int proxykv_destroy(proxykv_ctx* ctx) {
   if (!ctx) return PROXYKV_OK;
   std::vector<DeviceBuffer*> all = {&ctx->weight_blob, &ctx->q_bf16, &ctx->kctx_bf16, &ctx->krec_bf16,
-                                    &ctx->neg_lse,     &ctx->x_ws,   &ctx->yhat_ws};
+                                    &ctx->neg_lse,     &ctx->x_ws,   &ctx->yhat_ws, &ctx->topk_ws};
   for (pkv::MapperWorkspace& m : ctx->m)
     for (DeviceBuffer* b : {&m.h1, &m.z_local, &m.x, &m.xb, &m.qk, &m.vt, &m.ao, &m.tmp, &m.hid, &m.zg, &m.kv3}) all.push_back(b);
   bool any = ctx->ev_created || ctx->lanes_created;
@@ -498,7 +499,10 @@ int proxykv_score(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const 
   const int rc = validate_lengths(N, N_q, chunk);
   if (rc) return rc;
   PKV_HIP(ctx, hipSetDevice(ctx->cfg.device));
-  return score_impl(ctx, q_rec, k_ctx, k_rec, dtype, N, N_q, chunk, x_out, (hipStream_t)stream);
+  // stage timing describes a whole proxykv_prune: a score call on its own leaves no complete record behind
+  const int rcs = score_impl(ctx, q_rec, k_ctx, k_rec, dtype, N, N_q, chunk, x_out, (hipStream_t)stream);
+  for (int i = 0; i < PROXYKV_N_STAGES + 1; ++i) ctx->ev_recorded[i] = false;
+  return rcs;
 }
 
 int proxykv_score_self(proxykv_ctx* ctx, const void* q, const void* k, int32_t dtype, int64_t N, float* x_out, void* stream) {
@@ -507,7 +511,9 @@ int proxykv_score_self(proxykv_ctx* ctx, const void* q, const void* k, int32_t d
   const int rc = validate_lengths(N, N, N);
   if (rc) return rc;
   PKV_HIP(ctx, hipSetDevice(ctx->cfg.device));
-  return score_self_impl(ctx, q, k, dtype, N, x_out, (hipStream_t)stream);
+  const int rcs = score_self_impl(ctx, q, k, dtype, N, x_out, (hipStream_t)stream);
+  for (int i = 0; i < PROXYKV_N_STAGES + 1; ++i) ctx->ev_recorded[i] = false;
+  return rcs;
 }
 
 int proxykv_map(proxykv_ctx* ctx, const float* x, int64_t N, float* yhat, void* stream) {
@@ -523,8 +529,11 @@ int proxykv_topk(proxykv_ctx* ctx, const float* scores, int64_t rows, int64_t N,
                  void* stream) {
   if (!ctx || !scores || !idx_out) return PROXYKV_EINVAL;
   if (rows <= 0 || rows >= (1ll << 31) || N <= 0 || N >= (1ll << 31) - 4096 || K < 1 || K > N) return PROXYKV_EINVAL;
+  if (N > pkv::kTopkSingleMax && rows > 65535) return PROXYKV_EUNSUPPORTED;
   PKV_HIP(ctx, hipSetDevice(ctx->cfg.device));
-  PKV_HIP(ctx, pkv::launch_topk(scores, rows, N, K, idx_out, (hipStream_t)stream));
+  const int rc = ensure(ctx, ctx->topk_ws, pkv::topk_scratch_bytes(rows, N), (hipStream_t)stream);
+  if (rc) return rc;
+  PKV_HIP(ctx, pkv::launch_topk(scores, rows, N, K, idx_out, ctx->topk_ws.ptr, (hipStream_t)stream));
   return PROXYKV_OK;
 }
 
@@ -553,8 +562,11 @@ int proxykv_topk_pooled(proxykv_ctx* ctx, const float* scores, int64_t layers, i
   if (!ctx || !scores || !flat_out || !counts_out) return PROXYKV_EINVAL;
   if (layers <= 0 || heads <= 0 || N <= 0 || K < 1 || K > N) return PROXYKV_EINVAL;
   if (layers * heads >= (1ll << 31) || heads * N >= (1ll << 31) - 4096) return PROXYKV_EINVAL;
+  if (heads * N > pkv::kTopkSingleMax && layers > 65535) return PROXYKV_EUNSUPPORTED;
   PKV_HIP(ctx, hipSetDevice(ctx->cfg.device));
-  PKV_HIP(ctx, pkv::launch_topk(scores, layers, heads * N, heads * K, flat_out, (hipStream_t)stream));
+  const int rc = ensure(ctx, ctx->topk_ws, pkv::topk_scratch_bytes(layers, heads * N), (hipStream_t)stream);
+  if (rc) return rc;
+  PKV_HIP(ctx, pkv::launch_topk(scores, layers, heads * N, heads * K, flat_out, ctx->topk_ws.ptr, (hipStream_t)stream));
   PKV_HIP(ctx, pkv::launch_head_counts(flat_out, layers, heads, N, K, counts_out, (hipStream_t)stream));
   return PROXYKV_OK;
 }
@@ -599,11 +611,25 @@ int proxykv_prune(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const 
   if ((rc = score_impl(ctx, q_rec, k_ctx, k_rec, dtype, N, N_q, chunk, x, s))) return rc;
   if ((rc = map_impl(ctx, x, N, y, s))) return rc;
   if ((rc = mark(ctx, 3, s))) return rc;
-  PKV_HIP(ctx, pkv::launch_topk(y, rows, N, K, idx_out, s));
-  if ((rc = mark(ctx, 4, s))) return rc;
-  PKV_HIP(ctx, pkv::launch_compact(k_in, v_in, idx_out, rows, N, K, (int64_t)c.D * 2, k_out, v_out, s));
+  const int cpr = c.D * 2 / 16;
+  if (ctx->fused_select && 1024 % cpr == 0) {
+    // selection and gather in one launch: the workgroup that has written a stretch of a row's kept indices moves those
+    // tokens' K and V rows; the whole launch is booked as the compaction stage
+    if ((rc = mark(ctx, 4, s))) return rc;
+    PKV_HIP(ctx, pkv::launch_topk_gather(y, rows, N, K, idx_out, ctx->topk_ws.ptr, k_in, v_in, (int64_t)c.D * 2, k_out, v_out, s));
+  } else {
+    PKV_HIP(ctx, pkv::launch_topk(y, rows, N, K, idx_out, ctx->topk_ws.ptr, s));
+    if ((rc = mark(ctx, 4, s))) return rc;
+    PKV_HIP(ctx, pkv::launch_compact(k_in, v_in, idx_out, rows, N, K, (int64_t)c.D * 2, k_out, v_out, s));
+  }
   if ((rc = mark(ctx, 5, s))) return rc;
   if (K_host) *K_host = K;
+  return PROXYKV_OK;
+}
+
+int proxykv_set_fused_select(proxykv_ctx* ctx, int on) {
+  if (!ctx) return PROXYKV_EINVAL;
+  ctx->fused_select = on != 0;
   return PROXYKV_OK;
 }
 
@@ -637,6 +663,7 @@ const char* proxykv_strerror(int status) {
     case PROXYKV_ENOMEM: return "out of device memory";
     case PROXYKV_ESTATE: return "context not ready (mapper weights not set)";
     case PROXYKV_EHIP: return "HIP runtime error";
+    case PROXYKV_ELIMIT: return "size beyond a fixed limit of this entry point";
     default: return "unknown status";
   }
 }

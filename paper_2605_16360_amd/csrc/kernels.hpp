@@ -1,6 +1,7 @@
 // Launchers of the HIP kernels; each enqueues on `stream` and returns the launch's hipError_t.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 namespace pkv {
@@ -23,8 +24,17 @@ hipError_t launch_score_colmax(const uint16_t* q, const uint16_t* k_ctx, const f
 hipError_t launch_score_colsum(const uint16_t* q, const uint16_t* k_ctx, const float* neg_lse, float* x,
                                int L_s, int H_q, int H_kv, int d, int64_t N, int64_t N_q, bool causal,
                                hipStream_t stream);
-hipError_t launch_topk(const float* scores, int64_t rows, int64_t N, int64_t K, int32_t* idx_out,
+// Per-row Top-K.  Rows longer than 36 864 scores are split over several workgroups and need `scratch`
+// (topk_scratch_bytes(rows, N) bytes of device memory, any contents, 256-byte aligned; rows <= 65535 then).
+constexpr int64_t kTopkSingleMax = 36864;  // longest row one workgroup selects from
+size_t topk_scratch_bytes(int64_t rows, int64_t N);
+hipError_t launch_topk(const float* scores, int64_t rows, int64_t N, int64_t K, int32_t* idx_out, void* scratch,
                        hipStream_t stream);
+// The same selection with every workgroup gathering the token rows it kept: k_out[r, j, :] = k_in[r, idx[r, j], :] and
+// likewise v (row_bytes per token, 1024 / (row_bytes / 16) a whole number).
+hipError_t launch_topk_gather(const float* scores, int64_t rows, int64_t N, int64_t K, int32_t* idx_out, void* scratch,
+                              const void* k_in, const void* v_in, int64_t row_bytes, void* k_out, void* v_out,
+                              hipStream_t stream);
 
 hipError_t launch_compact(const void* k_in, const void* v_in, const int32_t* idx, int64_t rows, int64_t N,
                           int64_t K, int64_t row_bytes, void* k_out, void* v_out, hipStream_t stream);

@@ -2,7 +2,9 @@
 proxykv_prune over all layers), on outputs the CPU oracle can compute one by one.
 
 Every oracle input comes from the seeded generator (synth), never from the HIP path:
-  * scoring  - one whole (proxy layer, KV head) unit exactly where that takes seconds; on every
+  * scoring  - one whole (proxy layer, KV head) unit key by key (llama_8k, llama_32k, qwen32b_32k; at qwen_170k,
+               where one unit is 2.6e13 oracle flop, all 170 000 context keys of a unit against the first 4112
+               queries of its seven heads: two whole chunks and a ragged one of 16); on every
                workload the planted heavy hitters (their source query's softmax row is one matrix-vector
                product; the score lies between that probability and 1) and, for sampled queries at chunk
                starts, chunk ends and the ragged tail, the bound X[n] >= p_i(n) on all N keys at once;
@@ -281,7 +283,7 @@ def test_llama_32k_full_size():
 def test_qwen32b_32k_full_size():
     """Head dimension 128, groups of 6, chunks of 4096, 64 target layers paired with 28 proxy layers."""
     N = synth.CASES["qwen32b_32k"].N
-    _run_case("qwen32b_32k", units=[(0, 0), (13, 1), (27, 1)], full_unit=None,
+    _run_case("qwen32b_32k", units=[(0, 0), (27, 1)], full_unit=(13, 1),
               map_samples=[(0, 0, 1024), (27, N - 1024, N)], keep_ratio=0.5)
 
 
@@ -291,3 +293,101 @@ def test_qwen_170k_full_size():
     N = synth.CASES["qwen_170k"].N
     _run_case("qwen_170k", units=[(0, 0), (23, 1)], full_unit=None,
               map_samples=[(0, 0, 1024), (11, 84992, 86016), (23, N - 1024, N)])
+
+
+def test_qwen_170k_score_two_sided_on_all_context_keys():
+    """All 170 000 context keys of one (layer, KV head) of the qwen_170k workload, groups of seven heads, against the
+    oracle key by key, with the first 4112 reconstruction queries of every head (two whole chunks of 2048 and a ragged
+    chunk of 16): ragged key tiles, the ragged last chunk and the group reduction at the workload's own key count.
+    The whole unit (170 000 queries per head) is 2.6e13 oracle flop and is covered by bounds in the test above."""
+    case = synth.CASES["qwen_170k"]
+    l, h, nq = 17, 1, 2 * case.chunk + 16
+    sub = synth.scaled_case(case, name="qwen_170k_unit", L_s=1, H_q=case.G, H_kv=1, L_l=1, H_l=1, N_q=nq)
+    # the unit's own tensors: rows of the full workload's streams, generated unit by unit
+    G, N, d = case.G, case.N, case.d
+    q = torch.empty(1, G, nq, d, dtype=torch.bfloat16, device="cuda")
+    for g in range(G):
+        start = ((l * case.H_q + h * G + g) * case.N_q) * d
+        q[0, g] = synth.irwin_hall(synth.MASTER_SEED, synth.TID_Q_REC, start, nq * d, "cuda").view(nq, d).to(torch.bfloat16)
+    kc = synth.irwin_hall(synth.MASTER_SEED, synth.TID_K_CTX, ((l * case.H_kv + h) * N) * d, N * d, "cuda").view(1, 1, N, d)
+    kr = synth.irwin_hall(synth.MASTER_SEED, synth.TID_K_REC, ((l * case.H_kv + h) * case.N_q) * d, nq * d, "cuda").view(1, 1, nq, d)
+    # heavy hitters as in the workload: 340 context keys are three times a query of the group
+    rng = np.random.default_rng(170)
+    pos = rng.choice(N, size=case.n_planted, replace=False)
+    src = rng.choice(G * nq, size=case.n_planted, replace=False)
+    kc[0, 0, torch.from_numpy(pos).cuda()] = case.plant_scale * q[0].float().view(G * nq, d)[torch.from_numpy(src).cuda()]
+    kc, kr = kc.to(torch.bfloat16).contiguous(), kr.to(torch.bfloat16).contiguous()
+    for reduce, code in (("max", pk.PROXYKV_REDUCE_MAX), ("sum", pk.PROXYKV_REDUCE_SUM)):
+        cfg = pk.config_for_case(sub)
+        cfg.reduce = code
+        ctx = pk.proxykv_create(cfg)
+        x = pk.proxykv_score(ctx, q, kc, kr, case.chunk)
+        torch.cuda.synchronize()
+        ref = oracle.score_unit(q[0].double().cpu(), kc[0, 0].double().cpu(), kr[0, 0].double().cpu(), case.chunk, reduce=reduce)
+        _close(x[0, 0], ref, f"score {reduce}[qwen_170k] unit ({l}, {h}), {nq} queries")
+        if reduce == "max":
+            assert float(x[0, 0, torch.from_numpy(pos).cuda()].min()) > 0.5
+        pk.proxykv_destroy(ctx)
+
+
+def test_qwen32b_shape_score_two_sided_mid_size():
+    """Head width 128, groups of six, chunks of 4096 at N = N_q = 8192 (two chunks): every (layer, KV head) key by key,
+    max and sum forms, through the same kernels and column tiling as the qwen32b_32k workload."""
+    case = synth.scaled_case(synth.CASES["qwen32b_32k"], name="qwen32b_8k", L_s=2, L_l=2, N=8192, N_q=8192, n_planted=82)
+    q, kc, kr = synth.make_proxy_qk(case, device="cuda")
+    for reduce, code in (("max", pk.PROXYKV_REDUCE_MAX), ("sum", pk.PROXYKV_REDUCE_SUM)):
+        cfg = pk.config_for_case(case)
+        cfg.reduce = code
+        ctx = pk.proxykv_create(cfg)
+        x = pk.proxykv_score(ctx, q, kc, kr, case.chunk)
+        torch.cuda.synchronize()
+        ref = oracle.score(q.double().cpu(), kc.double().cpu(), kr.double().cpu(), case.chunk, reduce=reduce)
+        _close(x, ref, f"score {reduce}[qwen32b shapes, 8k]")
+        pk.proxykv_destroy(ctx)
+
+
+def test_prune_is_bit_identical_next_to_a_busy_second_stream():
+    """The paper's single-GPU regime (Sec. 4.3, App. A): the proxy side shares the device with the target's prefill
+    through streams.  One proxykv_prune (which itself spreads the mapper over up to four streams the context owns) runs
+    while a second stream loops large bf16 matrix products; scores, mapped scores, kept indices and the compacted
+    cache must equal those of a run on a quiet device bit for bit."""
+    case = synth.CASES["llama_8k"]
+    w = synth.make_mapper_weights(case.H_kv, case.H_l)
+    ctx = pk.proxykv_create(pk.config_for_case(case))
+    pk.proxykv_set_mapper_weights(ctx, w)
+    pk.proxykv_reserve(ctx, case.N, case.N_q)
+    q, kc, kr = synth.make_proxy_qk(case, device="cuda")
+    k_t, v_t = synth.make_target_kv(case, device="cuda")
+
+    def run(stream):
+        x = torch.empty(case.L_s, case.H_kv, case.N, dtype=torch.float32, device="cuda")
+        y = torch.empty(case.L_l, case.H_l, case.N, dtype=torch.float32, device="cuda")
+        k_out, v_out, idx, K = pk.proxykv_prune(ctx, q, kc, kr, case.chunk, 0.3, k_t, v_t, x_out=x, yhat_out=y, stream=stream)
+        return x, y, idx, k_out, v_out
+
+    main = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    quiet = run(main)
+    torch.cuda.synchronize()
+    a = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
+    b = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
+    c = torch.empty(8192, 8192, device="cuda", dtype=torch.bfloat16)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(side):
+        ev0.record(side)
+        for _ in range(60):                       # about 50 ms of stand-in prefill, longer than the prune
+            torch.matmul(a, b, out=c)
+        ev1.record(side)
+    pm0, pm1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    pm0.record(main)
+    busy = run(main)
+    pm1.record(main)
+    torch.cuda.synchronize()
+    # the two really ran at the same time: the prune ended before the side stream's loop did
+    assert ev0.elapsed_time(pm1) < ev0.elapsed_time(ev1), "the second stream was idle before the prune finished"
+    for name, g, r in zip(("x", "yhat", "idx", "k_out", "v_out"), busy, quiet):
+        same = torch.equal(g.view(torch.int16), r.view(torch.int16)) if g.dtype == torch.bfloat16 else torch.equal(g, r)
+        assert same, f"{name} differs when a second stream is busy"
+    pk.proxykv_destroy(ctx)

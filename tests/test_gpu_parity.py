@@ -58,9 +58,10 @@ def test_topk_bit_exact(N, K):
     assert torch.equal(got.cpu(), ref)
 
 
-@pytest.mark.parametrize("N", [36863, 36864, 36865, 40000])
+@pytest.mark.parametrize("N", [36863, 36864, 36865, 40000, 73729, 170000])
 def test_topk_bit_exact_around_the_kernel_switch(N):
-    """Rows of up to 36 864 scores take the register-resident kernel, longer ones the streaming kernel."""
+    """Rows of up to 36 864 scores are selected by one workgroup, longer ones are split over several (two parts, three
+    parts with a ragged last one, five parts)."""
     ctx = _ctx(synth.CASES["tiny"])
     g = torch.Generator().manual_seed(N)
     s = torch.randn(5, N, generator=g)
@@ -140,6 +141,27 @@ def test_pooled_budget_bit_exact():
                 for got, src in ((k, kv[0]), (v, kv[1])):
                     assert torch.equal(got[l, h, :c].cpu().view(torch.int16), src[l, h][tok].view(torch.int16)), (N, K, l, h)
                     assert torch.equal(got[l, h, c:].cpu().view(torch.int16), src[l, h, c:].view(torch.int16)), (N, K, l, h)
+
+
+def test_prune_selection_and_gather_in_one_launch_equals_two_launches():
+    """proxykv_prune with the Top-K kernel gathering the kept tokens itself (the default) against the same call with the
+    two kernels one after the other: same bits, for rows one workgroup selects and for rows split over several."""
+    for (N, keep) in ((700, 0.3), (40000, 0.25)):
+        case = synth.scaled_case(synth.CASES["llama_8k"], name=f"fused_{N}", L_s=1, H_q=2, H_kv=1, d=64, L_l=2, H_l=3, N=N, N_q=64,
+                                 chunk=64, n_planted=2)
+        q, kc, kr = synth.make_proxy_qk(case, device="cuda")
+        k_t, v_t = synth.make_target_kv(case, device="cuda")
+        ctx = _ctx(case, synth.make_mapper_weights(case.H_kv, case.H_l))
+        outs = []
+        for on in (True, False):
+            pk.proxykv_set_fused_select(ctx, on)
+            k_out, v_out, idx, K = pk.proxykv_prune(ctx, q, kc, kr, case.chunk, keep, k_t, v_t)
+            torch.cuda.synchronize()
+            outs.append((idx.clone(), k_out.view(torch.int16).clone(), v_out.view(torch.int16).clone()))
+        for a, b in zip(*outs):
+            assert torch.equal(a, b), N
+        assert torch.equal(outs[0][1].cpu(), oracle.compact(k_t.cpu(), outs[0][0].cpu()).view(torch.int16))
+        pk.proxykv_destroy(ctx)
 
 
 # ----------------------------------------------------------------------------------------------
