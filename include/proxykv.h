@@ -158,6 +158,21 @@ int proxykv_map(proxykv_ctx* ctx, const float* x, int64_t N, float* yhat, void* 
 int proxykv_topk(proxykv_ctx* ctx, const float* scores, int64_t rows, int64_t N, int64_t K,
                  int32_t* idx_out, void* stream);
 
+/* proxykv_topk for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same result, but the call allocates nothing (no hipMalloc, no hipFree, no
+ * workspace growth): the per-row histograms and counters that rows longer than 36 864 scores need live in a fixed
+ * array of 8 MiB inside the library's device image (every GPU the library runs on holds it until the process ends).
+ * Rows of up to 36 864 scores need none of it.  For longer rows the call needs
+ *     rows * (1040 + 257 * ceil(N / 36864)) * 4 bytes <= proxykv_topk_static_limit() = 8 MiB
+ * (901 rows of 170 000 scores, 677 of 262 144) and returns PROXYKV_ELIMIT beyond that, before any device work.
+ * All calls on one GPU share the array: calls that overlap in time on one GPU (different streams or contexts) race;
+ * calls on one stream are ordered and each clears what it needs with a kernel of its own (no memset node, so the
+ * call can be captured).  The first call on a device looks up the array's address (the runtime loads the device
+ * image then): make one call of any size before capturing. */
+int proxykv_topk_static(proxykv_ctx* ctx, const float* scores, int64_t rows, int64_t N, int64_t K,
+                        int32_t* idx_out, void* stream);
+size_t proxykv_topk_static_limit(void);
+
 /* Applies the mask to the target cache (Sec. 3, Sec. 4.3): for r < rows, j < K
  *   k_out[r, j, :] = k_in[r, idx[r, j], :]   and the same for v.
  *   k_in, v_in [rows, N, D] 16-bit elements; idx [rows, K] int32 in [0, N); k_out, v_out

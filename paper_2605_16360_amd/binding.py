@@ -20,7 +20,8 @@ PROXYKV_REDUCE_MAX, PROXYKV_REDUCE_SUM = 0, 1
 EXPORTS = [
     "proxykv_default_mapper", "proxykv_create", "proxykv_destroy", "proxykv_mapper_weight_count",
     "proxykv_set_mapper_weights", "proxykv_workspace_bytes", "proxykv_reserve", "proxykv_keep_count",
-    "proxykv_layer_pairing", "proxykv_score", "proxykv_score_self", "proxykv_map", "proxykv_topk", "proxykv_compact", "proxykv_compact_inplace",
+    "proxykv_layer_pairing", "proxykv_score", "proxykv_score_self", "proxykv_map", "proxykv_topk", "proxykv_topk_static",
+    "proxykv_topk_static_limit", "proxykv_compact", "proxykv_compact_inplace",
     "proxykv_mask", "proxykv_topk_pooled", "proxykv_compact_pooled", "proxykv_prune", "proxykv_set_fused_select",
     "proxykv_profile_enable", "proxykv_profile_read", "proxykv_strerror", "proxykv_last_hip_error",
 ]
@@ -69,6 +70,8 @@ def load() -> ctypes.CDLL:
     lib.proxykv_score_self.argtypes = [vp, vp, vp, i32, i64, vp, vp]
     lib.proxykv_map.argtypes = [vp, vp, i64, vp, vp]
     lib.proxykv_topk.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+    lib.proxykv_topk_static.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+    lib.proxykv_topk_static_limit.argtypes = []; lib.proxykv_topk_static_limit.restype = sz
     lib.proxykv_compact.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp, vp]
     lib.proxykv_compact_inplace.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp]
     lib.proxykv_mask.argtypes = [vp, vp, i64, i64, i64, vp, vp]
@@ -276,6 +279,19 @@ def proxykv_topk(ctx: Context, scores, K: int, idx_out=None, stream=None) -> tor
         idx_out = torch.empty(*scores.shape[:-1], K, dtype=torch.int32, device=scores.device)
     _check(load().proxykv_topk(ctx.handle, _dev_ptr(scores, "scores", torch.float32), rows, N, K,
                                _dev_ptr(idx_out, "idx_out", torch.int32), _stream_ptr(stream)), "proxykv_topk", ctx.handle)
+    return idx_out
+
+
+def proxykv_topk_static_limit() -> int:
+    return int(load().proxykv_topk_static_limit())
+
+
+def proxykv_topk_static(ctx: Context, scores, K: int, idx_out, stream=None) -> torch.Tensor:
+    """proxykv_topk without any allocation: idx_out must be passed in; the library's scratch is a fixed device array."""
+    N = scores.shape[-1]
+    rows = scores.numel() // N
+    _check(load().proxykv_topk_static(ctx.handle, _dev_ptr(scores, "scores", torch.float32), rows, N, K,
+                                      _dev_ptr(idx_out, "idx_out", torch.int32), _stream_ptr(stream)), "proxykv_topk_static", ctx.handle)
     return idx_out
 
 

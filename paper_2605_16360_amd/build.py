@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libproxykv.so")
-SOURCES = ["api.cpp", "score_lse.hip", "score_colmax.hip", "topk.hip", "compact.hip", "mapper.hip"]
+SOURCES = ["api.cpp", "score_lse.hip", "score_colmax.hip", "topk.hip", "topk_static.hip", "compact.hip", "mapper.hip"]
 # packed fp32 VALU ops are switched off for every device compile
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]
