@@ -226,10 +226,11 @@ int proxykv_prune(proxykv_ctx* ctx, const void* q_rec, const void* k_ctx, const 
                   const void* k_in, const void* v_in, void* k_out, void* v_out, int32_t* idx_out,
                   float* x_out, float* yhat_out, int64_t* K_host, void* stream);
 
-/* Sec. 4.3 names a Top-K kernel that materialises the mask in place.  With this switch on (the default) proxykv_prune
- * runs selection and gather as ONE launch: the workgroup that has written a stretch of a row's kept indices moves
- * those tokens' K and V rows itself (stage timing then books the whole launch as the compaction stage).  Off: the
- * kernels of proxykv_topk and proxykv_compact one after the other.  Same bits either way. */
+/* Sec. 4.3 names a Top-K kernel that materialises the mask in place.  With this switch on proxykv_prune runs
+ * selection and gather as ONE launch: the workgroup that has written a stretch of a row's kept indices moves those
+ * tokens' K and V rows itself (stage timing then books the whole launch as the compaction stage).  Off (the default:
+ * measured faster, a row's gather is then spread over many small workgroups): the kernels of proxykv_topk and
+ * proxykv_compact one after the other.  Same bits either way. */
 int proxykv_set_fused_select(proxykv_ctx* ctx, int on);
 
 /* Stage timing of proxykv_prune, for benchmarks.  With timing switched on, proxykv_prune records a

@@ -92,7 +92,7 @@ struct proxykv_ctx {
   pkv::DeviceBuffer x_ws;                          // fp32 [L_s, H_kv, N]
   pkv::DeviceBuffer yhat_ws;                       // fp32 [L_l, H_l, N]
   pkv::DeviceBuffer topk_ws;                       // per-row histograms and counters of the Top-K of rows split over workgroups
-  bool fused_select = true;                        // proxykv_prune: selection and gather in one launch
+  bool fused_select = false;                       // proxykv_prune: selection and gather in one launch (measured slower)
   pkv::MapperWorkspace m[pkv::kMapLanes];          // one per lane; only the lanes a length needs are allocated
   // lanes 1 .. kMapLanes-1: streams (default priority, non-blocking) and the events that fork them from and join
   // them into the caller's stream

@@ -193,6 +193,14 @@ def _check_fused_equals_stages(case, ctx, q, kc, kr, k_t, v_t, keep_ratio):
     y = torch.empty(case.L_l, case.H_l, case.N, dtype=torch.float32, device=dev)
     k_out, v_out, idx, K = pk.proxykv_prune(ctx, q, kc, kr, case.chunk, keep_ratio, k_t, v_t, x_out=x, yhat_out=y)
     torch.cuda.synchronize()
+    # and with the Top-K kernel gathering the kept tokens itself
+    pk.proxykv_set_fused_select(ctx, True)
+    k_f, v_f, idx_f, _ = pk.proxykv_prune(ctx, q, kc, kr, case.chunk, keep_ratio, k_t, v_t)
+    pk.proxykv_set_fused_select(ctx, False)
+    torch.cuda.synchronize()
+    assert torch.equal(idx_f, idx) and torch.equal(k_f.view(torch.int16), k_out.view(torch.int16))
+    assert torch.equal(v_f.view(torch.int16), v_out.view(torch.int16))
+    del k_f, v_f, idx_f
     x2 = pk.proxykv_score(ctx, q, kc, kr, case.chunk)
     y2 = pk.proxykv_map(ctx, x2)
     idx2 = pk.proxykv_topk(ctx, y2.view(-1, case.N), K).view(case.L_l, case.H_l, K)
