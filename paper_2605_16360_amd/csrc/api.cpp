@@ -77,8 +77,8 @@ int ensure(proxykv_ctx* ctx, DeviceBuffer& b, size_t bytes, hipStream_t stream) 
 }
 
 struct Sizes {
-  size_t neg_lse, x_ws, yhat_ws, h1, z_local, x, xb, qk, vt, ao, tmp, hid, zg, kv3;
-  size_t mapper() const { return h1 + z_local + x + xb + qk + vt + ao + tmp + hid + zg + kv3; }  // one lane's activations
+  size_t neg_lse, x_ws, yhat_ws, h1, z_local, x, xb, qk, vt, ao, hid, zg, kv3, range;
+  size_t mapper() const { return h1 + z_local + x + xb + qk + vt + ao + hid + zg + kv3 + range; }  // one lane's activations
   size_t total() const { return neg_lse + x_ws + yhat_ws + mapper(); }
 };
 
@@ -95,13 +95,13 @@ Sizes workspace_sizes(const proxykv_config& c, int64_t N, int64_t N_q) {
   s.z_local = Npad * dt * 4;
   s.x = Tp * dt * 4;
   s.xb = Tp * dt * 2;
-  s.qk = Tp * 3 * dt * 2;
+  s.qk = Tp * 2 * dt * 2;
   s.vt = (size_t)n_win * dt * (size_t)c.win * 2;
   s.ao = Tp * dt * 2;
-  s.tmp = Tp * dt * 4;
   s.hid = Tp * (size_t)c.d_ffn * 2;
   s.zg = Np * dt * 2;
   s.kv3 = Npad * (size_t)pkv::kv3_stride(c) * 4;
+  s.range = 256;
   return s;
 }
 
@@ -136,10 +136,10 @@ int reserve_all(proxykv_ctx* ctx, int64_t N, int64_t N_q, bool score_part, bool 
     if ((rc = ensure(ctx, m.qk, s.qk, stream))) return rc;
     if ((rc = ensure(ctx, m.vt, s.vt, stream))) return rc;
     if ((rc = ensure(ctx, m.ao, s.ao, stream))) return rc;
-    if ((rc = ensure(ctx, m.tmp, s.tmp, stream))) return rc;
     if ((rc = ensure(ctx, m.hid, s.hid, stream))) return rc;
     if ((rc = ensure(ctx, m.zg, s.zg, stream))) return rc;
     if ((rc = ensure(ctx, m.kv3, s.kv3, stream))) return rc;
+    if ((rc = ensure(ctx, m.range, s.range, stream))) return rc;
    }
   }
   return rc;
@@ -303,7 +303,7 @@ int proxykv_destroy(proxykv_ctx* ctx) {
   std::vector<DeviceBuffer*> all = {&ctx->weight_blob, &ctx->q_bf16, &ctx->kctx_bf16, &ctx->krec_bf16,
                                     &ctx->neg_lse,     &ctx->x_ws,   &ctx->yhat_ws, &ctx->topk_ws};
   for (pkv::MapperWorkspace& m : ctx->m)
-    for (DeviceBuffer* b : {&m.h1, &m.z_local, &m.x, &m.xb, &m.qk, &m.vt, &m.ao, &m.tmp, &m.hid, &m.zg, &m.kv3}) all.push_back(b);
+    for (DeviceBuffer* b : {&m.h1, &m.z_local, &m.x, &m.xb, &m.qk, &m.vt, &m.ao, &m.hid, &m.zg, &m.kv3, &m.range}) all.push_back(b);
   bool any = ctx->ev_created || ctx->lanes_created;
   for (DeviceBuffer* b : all) any = any || b->ptr;
   if (any) {
@@ -364,6 +364,18 @@ int proxykv_set_mapper_weights(proxykv_ctx* ctx, const float* blob, size_t n_flo
   const size_t o_c1w = st.put_f32(c1w, C1 * Hs * 3);
   size_t o_s1, o_h1;
   fold(c1b, g1, b1, m1, v1, C1, &o_s1, &o_h1);
+  // bound of the first block's output, |GELU(y)| <= |y| <= |scale_c| * sum |w_c| * max|x| + |shift_c|
+  double cw = 0.0, cs = 0.0;
+  for (size_t ch = 0; ch < C1; ++ch) {
+    const double sgn = (double)g1[ch] / sqrt((double)v1[ch] + eps), sc = fabs(sgn);
+    double wsum = 0.0;
+    for (size_t i = 0; i < Hs * 3; ++i) wsum += fabs((double)c1w[ch * Hs * 3 + i]);
+    const double sh = fabs(((double)c1b[ch] - (double)m1[ch]) * sgn + (double)b1[ch]);
+    if (sc * wsum > cw) cw = sc * wsum;
+    if (sh > cs) cs = sh;
+  }
+  ctx->w.stem_cw = (float)(cw * 1.0001);
+  ctx->w.stem_cs = (float)(cs * 1.0001 + 1e-6);
   const float* c2w = take(D * C1 * 3);
   const float* c2b = take(D);
   const float *g2 = take(D), *b2 = take(D), *m2 = take(D), *v2 = take(D);

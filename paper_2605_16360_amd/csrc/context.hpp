@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include <vector>
 
@@ -33,6 +34,7 @@ struct EncoderLayerWeights {
 struct MapperWeights {
   const float* conv1_w;                  // fp32 [c_mid, H_kv*3]
   const float *bn1_scale, *bn1_shift;    // batch norm and conv bias folded: y = conv * scale + shift
+  float stem_cw = 0.0f, stem_cs = 0.0f;  // |first conv block's output| <= stem_cw * max|x| + stem_cs (host values)
   const uint16_t* conv2_w;               // fp16 [d_time, 3*c_mid], k index = tap * c_mid + channel
   const float *bn2_scale, *bn2_shift;
   std::vector<EncoderLayerWeights> enc;
@@ -54,8 +56,13 @@ inline int kv3_stride(const proxykv_config& c) { return (2 * c.H_kv * c.d_head_x
 // take two, which lets one layer's bandwidth-bound kernels (layer norm, V transpose) run under the other's GEMMs and
 // attention (measured at N = 32 768: 91 ms against 97 ms with one lane, no further gain with four).
 constexpr int kMapLanes = 4;
+// The environment variable PROXYKV_MAP_LANES (1 .. kMapLanes) overrides the choice, for measurements.
 inline int map_lanes(int64_t window_rows, int distinct_layers) {
-  const int lanes = window_rows * kMapLanes <= 131072 ? kMapLanes : 2;
+  int lanes = window_rows * kMapLanes <= 131072 ? kMapLanes : 2;
+  if (const char* env = getenv("PROXYKV_MAP_LANES")) {
+    const int v = atoi(env);
+    if (v >= 1 && v <= kMapLanes) lanes = v;
+  }
   return lanes < distinct_layers ? lanes : (distinct_layers > 0 ? distinct_layers : 1);
 }
 
@@ -64,13 +71,13 @@ struct MapperWorkspace {
   DeviceBuffer z_local;  // fp32 [N, d_time]
   DeviceBuffer x;        // fp32 [T, d_time]     residual stream over all window rows
   DeviceBuffer xb;       // fp16 [T, d_time]     fp16 copy feeding the GEMMs
-  DeviceBuffer qk;       // fp16 [T, 3*d_time]   q, k and v of the current layer
+  DeviceBuffer qk;       // fp16 [T, 2*d_time]   q and k of the current layer
   DeviceBuffer vt;       // fp16 [n_win, heads, 64, win]  v transposed per window and head
   DeviceBuffer ao;       // fp16 [T, d_time]     attention output
-  DeviceBuffer tmp;      // fp32 [T, d_time]     pre-norm sums
   DeviceBuffer hid;      // fp16 [T, d_ffn]
   DeviceBuffer zg;       // fp16 [N, d_time]     overlap-averaged encoder output
   DeviceBuffer kv3;      // fp32 [N, kv3_stride]  stage-3 keys then values of every slot, then padding
+  DeviceBuffer range;    // 3 words: largest |score| of the layer (bits), 2^-s and 2^s of the stem's range exponent
 };
 
 }  // namespace pkv

@@ -1,9 +1,11 @@
 // HybridAxialMapper forward (paper Sec. 4.1) for one proxy layer at a time:
 //   stage 1  conv stem            stem_conv1_kernel (fp32 ALU) + conv 2 as an fp16 MFMA GEMM whose A rows
 //                                 are overlapping 3-token spans of the padded conv-1 output
-//   stage 2  time-axis encoder    gather_pe_kernel, then per layer: QKV GEMM -> window attention ->
-//                                 out-proj GEMM (+residual) -> LayerNorm -> FFN GEMMs -> LayerNorm;
-//                                 all sliding windows of the layer are batched along the GEMM M axis
+//   stage 2  time-axis encoder    gather_pe_kernel, then per layer: QKV GEMM (writes q, k row-major and v transposed
+//                                 for the attention's second product) -> window attention -> out-proj GEMM whose
+//                                 epilogue adds the residual and normalises the row -> FFN-1 GEMM -> FFN-2 GEMM
+//                                 with the same epilogue; all sliding windows of the layer are batched along the
+//                                 GEMM M axis
 //            overlap averaging    overlap_avg_kernel
 //   stage 3  head-axis attention  K/V projection GEMM + stage3_kernel (per token, fp32 ALU)
 // Matrix products take IEEE half (fp16) operands and accumulate in fp32 on v_mfma_f32_32x32x16_f16; the
@@ -28,11 +30,45 @@ __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + e
 
 __device__ __forceinline__ uint16_t to_h(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
 
-// 8 chunks of 16 bytes per 128-byte LDS row, XOR-swizzled (see score.hip)
+// 8 chunks of 16 bytes per 128-byte LDS row, XOR-swizzled so that 16-byte tile stores and MFMA fragment reads
+// (32 consecutive rows, same chunk) both spread over all LDS banks
 __device__ __forceinline__ int swz8(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
 // ------------------------------------------------------------------------------------------
-// stage 1, first convolution: h1[t+1, c] = half(GELU(scale[c] * sum_{h,tap} w[c,h,tap] * x[h, t+tap-1] + shift[c]))
+// Range of the first convolution's output.  The scores of Sec. 3 in their sum form are not bounded by one (an
+// attention sink collects up to G * N_q), so GELU(BN(conv1(x))) can exceed what IEEE half holds.  The operand of the
+// second convolution is therefore stored as half(h1 * 2^-s) with one exponent s per proxy layer, taken from the
+// largest score of the layer, and the second convolution's per-channel scale is multiplied by 2^s: exact, since only
+// the exponent moves.  s = 0 (nothing changes) whenever the bound below stays under 2^15.
+//   slot[0]: bits of max |x| (atomicMax, cleared again by stem_scale_kernel), slot[1] = 2^-s, slot[2] = 2^s (floats)
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ x, int64_t n, uint32_t* __restrict__ slot) {
+  uint32_t m = 0;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const uint32_t a = __float_as_uint(x[i]) & 0x7fffffffu;
+    m = a > m ? a : m;
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const uint32_t o = __shfl_xor(m, off, 64);
+    m = o > m ? o : m;
+  }
+  if ((threadIdx.x & 63) == 0) atomicMax(slot, m);
+}
+
+// |h1| <= |scale_c| * sum |w_c| * max|x| + |shift_c| <= cw * max|x| + cs  (|GELU(y)| <= |y|)
+__global__ void stem_scale_kernel(uint32_t* __restrict__ slot, float cw, float cs) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const float bound = __builtin_fmaf(cw, __uint_as_float(slot[0]), cs);
+  const int e = (int)((__float_as_uint(bound) >> 23) & 255u) - 127;  // floor(log2(bound)); 128 for inf or NaN
+  const int sh = e >= 15 ? e - 14 : 0;                                 // bound * 2^-sh < 2^15
+  slot[1] = (uint32_t)(127 - sh) << 23;
+  slot[2] = (uint32_t)(127 + sh) << 23;
+  slot[0] = 0u;
+}
+
+// ------------------------------------------------------------------------------------------
+// stage 1, first convolution: h1[t+1, c] = half(2^-s * GELU(scale[c] * sum_{h,tap} w[c,h,tap] * x[h, t+tap-1] + shift[c]))
 // rows 0 and N+1 of h1 are zero (the padding of the second convolution).
 // grid ceil(N / 64), 256 threads; thread owns channels tid, tid+256, ...
 // ------------------------------------------------------------------------------------------
@@ -41,9 +77,11 @@ constexpr int kMaxHs = 16;
 
 __global__ __launch_bounds__(256) void stem_conv1_kernel(const float* __restrict__ x, const float* __restrict__ w,
                                                           const float* __restrict__ scale,
-                                                          const float* __restrict__ shift, uint16_t* __restrict__ h1,
-                                                          int H_s, int N, int c_mid) {
+                                                          const float* __restrict__ shift,
+                                                          const float* __restrict__ range_slot,
+                                                          uint16_t* __restrict__ h1, int H_s, int N, int c_mid) {
   __shared__ float xs[kMaxHs][kStemTok + 2];
+  const float down = range_slot[1];  // 2^-s
   const int t0 = blockIdx.x * kStemTok;
   for (int i = threadIdx.x; i < H_s * (kStemTok + 2); i += 256) {
     const int h = i / (kStemTok + 2), tt = i % (kStemTok + 2);
@@ -66,7 +104,7 @@ __global__ __launch_bounds__(256) void stem_conv1_kernel(const float* __restrict
           acc = __builtin_fmaf(wr[h * 3 + 2], xs[h][tt + 2], acc);
         }
       }
-      h1[(size_t)(t0 + tt + 1) * c_mid + c] = to_h(gelu_erf(__builtin_fmaf(acc, sc, sh)));
+      h1[(size_t)(t0 + tt + 1) * c_mid + c] = to_h(gelu_erf(__builtin_fmaf(acc, sc, sh)) * down);
     }
     if (blockIdx.x == 0) h1[c] = 0;
     if (blockIdx.x == gridDim.x - 1) h1[(size_t)(N + 1) * c_mid + c] = 0;
@@ -77,10 +115,11 @@ __global__ __launch_bounds__(256) void stem_conv1_kernel(const float* __restrict
 // fp16 GEMM  C[M, Nn] = A[M, K] * W[Nn, K]^T  (+ epilogue), fp32 accumulation.
 // A rows start lda elements apart (lda < K gives the overlapping rows of the second convolution).
 //
-// Persistent kernel, one 512-thread workgroup per CU.  Block tile 256 (rows of A) x 256 (rows of W),
-// K step 64 (full 128-byte lines per row), 8 waves in 4 x 2, each 64 x 128 = 2 x 4 MFMA tiles.  A tile
-// of this shape needs 1 byte from L2 per 128 flop; smaller tiles are bound by the L2 -> CU path, not by
-// the matrix pipe.
+// Persistent kernel, one 512-thread workgroup per CU.  Block tile BM (rows of A) x BN (rows of W), 256 x 256 or
+// 128 x 512, K step 64 (full 128-byte lines per row), 8 waves, each 64 x 128 = 2 x 4 MFMA tiles.  A tile
+// of this size needs 1 byte from L2 per 100 to 128 flop; smaller tiles are bound by the L2 -> CU path, not by
+// the matrix pipe.  The 128 x 512 shape spans a whole row of the encoder's width, so its epilogue can normalise
+// the row (residual add + LayerNorm) before anything goes to memory.
 //
 // The A rows go on the MFMA M axis and the W rows on the N axis, so a lane owns output COLUMNS.  The
 // W rows of a wave's 128-column block are staged in the order n = 4*l + jn (l = lane & 31, jn = MFMA
@@ -89,7 +128,7 @@ __global__ __launch_bounds__(256) void stem_conv1_kernel(const float* __restrict
 // buffers have their row count padded to a multiple of 256, so the epilogue has no row predicate; rows
 // at and past M are written with values that nobody reads.
 //
-// The K steps of all tiles of a workgroup form one stream: two LDS stages of 64 KB and ONE barrier
+// The K steps of all tiles of a workgroup form one stream: two LDS stages (64 or 80 KB each) and ONE barrier
 // per step.  A step is four phases of 8 MFMAs; the fragments of phase kk+1 are read from LDS between
 // the MFMAs of phase kk (phase 3 reads phase 0 of the next step, behind the barrier), step s+1 goes
 // from registers to LDS during phase 2 and each register is refilled with its part of step s+2 right
@@ -98,46 +137,76 @@ __global__ __launch_bounds__(256) void stem_conv1_kernel(const float* __restrict
 //
 // Tile order: blocks are dealt round-robin to the 8 XCDs by the hardware, so XCD x = block % 8 takes the
 // row tiles x, x+8, ... and its workgroups take that list's (row tile, column tile) pairs round-robin:
-// the Nn / 256 column tiles of one row tile run at the same time on one XCD and share its L2 copy of
+// the Nn / BN column tiles of one row tile run at the same time on one XCD and share its L2 copy of
 // the A rows.
-// K % 64 == 0, Nn % 256 == 0.
+// K % 64 == 0, Nn % BN == 0.
 // ------------------------------------------------------------------------------------------
 enum Epilogue {
-  kEpiAffineGeluF32,  // out_f32 = GELU(acc * p0[n] + p1[n])                       (second stem convolution)
-  kEpiBiasH,          // out_h = acc + p0[n]
+  kEpiAffineGeluF32,  // out_f32 = GELU(acc * (p0[n] * *p2) + p1[n])                 (second stem convolution)
+  kEpiQkvH,           // columns below 2 * d_time: out_h[m, n] = half(acc + p0[n]), rows ldc apart (q and k);
+                      // the others (v): out_v in the transposed, key-permuted layout of the attention kernel
   kEpiBiasReluH,      // out_h = relu(acc + p0[n])
-  kEpiBiasF32         // out_f32 = acc + p0[n]
+  kEpiBiasF32,        // out_f32 = acc + p0[n]
+  kEpiResLn           // BN = 512: y = LayerNorm(res[m, :] + acc + p0) * g + b -> out_f32 (may be res) and out_h
 };
 
 struct EpiArgs {
   const float* p0;
   const float* p1;
+  const float* p2;
+  const float* g;
+  const float* b;
+  const float* res;
   float* out_f32;
   uint16_t* out_h;
+  uint16_t* out_v;
+  int ldc;  // elements between output rows
 };
 
 // epilogue stores bypass L2 allocation: the output is not read again by this kernel and would evict W and A rows
 #define PKV_ST(ptr, val) __builtin_nontemporal_store((val), (ptr))
 
-constexpr int kGemmBM = 256, kGemmBN = 256, kGemmBK = 64;
-constexpr int kGemmStageU4 = (kGemmBM + kGemmBN) * (kGemmBK / 8);  // 16-byte units per stage
+constexpr int kGemmBK = 64;
 constexpr int kXcds = 8;
 
-template <int EPI>
+// Sum of v[0..15] over the 32 lanes that share bit 5 of the lane number, sixteen sums at once: in every step a lane
+// keeps the half of its values that its own lane bit selects, hands the other half to the partner and adds what it
+// receives; after four steps it holds one value, the row (lane & 31) >> 1 of the sixteen, summed over sixteen lanes,
+// and the last step adds the neighbour's.  31 exchanges instead of 80.
+__device__ __forceinline__ float reduce16_over_lanes(float (&v)[16], int l32) {
+  static_for<4>([&](auto sc) {
+    constexpr int step = decltype(sc)::value, n = 8 >> step, mask = 16 >> step;
+    const bool up = (l32 & mask) != 0;
+#pragma unroll
+    for (int j = 0; j < n; ++j) {
+      const float send = up ? v[j] : v[j + n];
+      const float keep = up ? v[j + n] : v[j];
+      v[j] = keep + __shfl_xor(send, mask, 64);
+    }
+  });
+  return v[0] + __shfl_xor(v[0], 1, 64);
+}
+
+template <int EPI, int BM, int BN>
 __global__ __launch_bounds__(512, 1) void gemm_f16_kernel(const uint16_t* __restrict__ A, int lda,
                                                             const uint16_t* __restrict__ W, int M, int Nn, int K,
                                                             EpiArgs ep) {
+  constexpr int WM = BM / 64, WN = 8 / WM;       // waves along M and N
+  constexpr int NA = BM / 64, NS = (BM + BN) / 64;  // 64-row parts of a stage: A parts, then W parts
+  constexpr int kStageU4 = (BM + BN) * (kGemmBK / 8);  // 16-byte units per stage
+  static_assert(WM * WN == 8 && BN / WN == 128, "a wave computes 64 x 128");
+  static_assert(EPI != kEpiResLn || BN == kDT, "the normalising epilogue needs the whole row in one tile");
   extern __shared__ u32x4 lds[];  // 2 stages
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int n_tiles = Nn / kGemmBN;
+  const int wm = wave / WN, wn = wave % WN;
+  const int n_tiles = Nn / BN;
   const int nk = K / kGemmBK;
   const int xcd = blockIdx.x % kXcds, wg = blockIdx.x / kXcds, wg_per_xcd = gridDim.x / kXcds;
   // tile `it` of this workgroup: entry it * wg_per_xcd + wg of the XCD's list
   auto tile_of = [&](int it, int& m0, int& n0) {
     const int u = it * wg_per_xcd + wg;
-    m0 = ((u / n_tiles) * kXcds + xcd) * kGemmBM;
-    n0 = (u % n_tiles) * kGemmBN;
+    m0 = ((u / n_tiles) * kXcds + xcd) * BM;
+    n0 = (u % n_tiles) * BN;
     return m0 < M;
   };
   int my_tiles = 0;
@@ -148,22 +217,22 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_kernel(const uint16_t* __rest
   const int total = my_tiles * nk;
   if (total == 0) return;
 
-  // staging: thread t moves chunk t % 8 of LDS rows t / 8 + 64 * i (i < 4: A rows, i >= 4: W rows).
-  // LDS row wl = 64 (i - 4) + t / 8 of the W part holds W row n0 + 128 (wl / 128) + 4 (wl % 32) + (wl % 128) / 32.
+  // staging: thread t moves chunk t % 8 of LDS rows t / 8 + 64 * i (i < NA: A rows, i >= NA: W rows).
+  // LDS row wl = 64 (i - NA) + t / 8 of the W part holds W row n0 + 128 (wl / 128) + 4 (wl % 32) + (wl % 128) / 32.
   const int srow = tid >> 3, sch = tid & 7;
   const int sslot = srow * 8 + (sch ^ swz8(srow));  // swz8(srow + 64 * i) == swz8(srow)
-  u32x4 rg[8];
+  u32x4 rg[NS];
   int f_m0 = 0, f_n0 = 0, f_k = 0, f_it = 0;  // position of the next step to fetch
   tile_of(0, f_m0, f_n0);
   auto fetch_one = [&](int i) {
     const int k0 = f_k * kGemmBK + sch * 8;
-    if (i < 4) {
+    if (i < NA) {
       int m = f_m0 + srow + 64 * i;
       m = m < M ? m : M - 1;
       rg[i] = *reinterpret_cast<const u32x4*>(A + (size_t)m * lda + k0);
     } else {
-      const int wl = srow + 64 * (i - 4);
-      const int n = f_n0 + (wl & 128) + 4 * (wl & 31) + ((wl & 127) >> 5);
+      const int wl = srow + 64 * (i - NA);
+      const int n = f_n0 + (wl & ~127) + 4 * (wl & 31) + ((wl & 127) >> 5);
       rg[i] = *reinterpret_cast<const u32x4*>(W + (size_t)n * K + k0);
     }
   };
@@ -196,22 +265,25 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_kernel(const uint16_t* __rest
     tile_of(it < my_tiles ? it : my_tiles - 1, m0, n0);
     const int n = n0 + wn * 128 + 4 * l32;
     p0 = *reinterpret_cast<const f32x4*>(ep.p0 + n);
-    if constexpr (EPI == kEpiAffineGeluF32) p1 = *reinterpret_cast<const f32x4*>(ep.p1 + n);
+    if constexpr (EPI == kEpiAffineGeluF32) {
+      p0 *= *ep.p2;
+      p1 = *reinterpret_cast<const f32x4*>(ep.p1 + n);
+    }
   };
   load_bias(0);
 
   // prologue: step 0 to LDS, step 1 in registers, fragments of (step 0, phase 0) in registers
 #pragma unroll
-  for (int i = 0; i < 8; ++i) fetch_one(i);
+  for (int i = 0; i < NS; ++i) fetch_one(i);
   fetch_advance();
 #pragma unroll
-  for (int i = 0; i < 8; ++i) lds[sslot + 64 * 8 * i] = rg[i];
+  for (int i = 0; i < NS; ++i) lds[sslot + 64 * 8 * i] = rg[i];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) fetch_one(i);
+  for (int i = 0; i < NS; ++i) fetch_one(i);
   fetch_advance();
   __syncthreads();
   const int fsw = swz8(l32);  // all fragment rows of this lane are l32 plus a multiple of 32
-  const int xrow = (wm * 64 + l32) * 8, wrow = (kGemmBM + wn * 128 + l32) * 8;
+  const int xrow = (wm * 64 + l32) * 8, wrow = (BM + wn * 128 + l32) * 8;
   f16x8 fx[2][2], fw[2][4];
   auto read_frag = [&](const u32x4* st, int kk, int set, int which) {
     const int slot = (kk * 2 + half) ^ fsw;
@@ -222,8 +294,8 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_kernel(const uint16_t* __rest
   for (int wh = 0; wh < 6; ++wh) read_frag(lds, 0, 0, wh);
 
   for (int s = 0; s < total; ++s) {
-    const u32x4* st = lds + (s & 1) * kGemmStageU4;
-    u32x4* st_next = lds + ((s + 1) & 1) * kGemmStageU4;
+    u32x4* st = lds + (s & 1) * kStageU4;
+    u32x4* st_next = lds + ((s + 1) & 1) * kStageU4;
     static_for<4>([&](auto kc) {
       constexpr int kk = decltype(kc)::value, cur = kk & 1, nxt = cur ^ 1;
       if constexpr (kk == 3) {
@@ -241,6 +313,10 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_kernel(const uint16_t* __rest
           // the register is refilled as soon as it is free: a whole step lies between a load and its use
           st_next[sslot + 64 * 8 * j] = rg[j];
           fetch_one(j);
+          if constexpr (j + 8 < NS) {
+            st_next[sslot + 64 * 8 * (j + 8)] = rg[j + 8];
+            fetch_one(j + 8);
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       });
@@ -252,82 +328,120 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_kernel(const uint16_t* __rest
     int m0, n0;
     tile_of(s / nk, m0, n0);
     const int n = n0 + wn * 128 + 4 * l32;
+    if constexpr (EPI == kEpiResLn) {
+      // (1) pre-norm sum in place, acc += bias + residual row, and (2) row sums and sums of squares: four columns in
+      // the lane, 32 lanes by exchange, 4 waves through LDS (the stage that this step has used up is free until
+      // phase 2 of the next step)
+      struct Pair {
+        float s1, s2;
+      };
+      Pair* red = reinterpret_cast<Pair*>(st);  // [128 rows][4 waves along N]
+      int own_row[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const size_t ob = (size_t)(m0 + wm * 64 + i * 32 + half * 4) * Nn + n;
+      for (int i = 0; i < 2; ++i) {
+        const float* rb = ep.res + (size_t)(m0 + wm * 64 + i * 32 + half * 4) * kDT + n;
 #pragma unroll
-      for (int qd = 0; qd < 4; ++qd) {
+        for (int qd = 0; qd < 4; ++qd) {
+          f32x4 rv[4];
 #pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-          const int r = qd * 4 + e4;
+          for (int e4 = 0; e4 < 4; ++e4) rv[e4] = *reinterpret_cast<const f32x4*>(rb + (size_t)(qd * 8 + e4) * kDT);
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4)
+#pragma unroll
+            for (int jn = 0; jn < 4; ++jn) acc[i][jn][qd * 4 + e4] += rv[e4][jn] + p0[jn];
+        }
+        float t[2];
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+          float sv[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float a0 = acc[i][0][r], a1 = acc[i][1][r], a2 = acc[i][2][r], a3 = acc[i][3][r];
+            sv[r] = which == 0 ? (a0 + a1) + (a2 + a3) : (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+          }
+          t[which] = reduce16_over_lanes(sv, l32);
+        }
+        own_row[i] = ((wm * 2 + i) * 2 + half) * 16 + (l32 >> 1);
+        if ((l32 & 1) == 0) red[own_row[i] * 4 + wn] = Pair{t[0], t[1]};
+      }
+      __syncthreads();
+      float mean_o[2], rstd_o[2];  // of the row this lane reduced
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(&red[own_row[i] * 4]);
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(&red[own_row[i] * 4 + 2]);
+        const float sum = (lo[0] + lo[2]) + (hi[0] + hi[2]), sq = (lo[1] + lo[3]) + (hi[1] + hi[3]);
+        const float mu = sum * (1.0f / kDT);
+        const float var = __builtin_fmaxf(__builtin_fmaf(-mu, mu, sq * (1.0f / kDT)), 0.0f);
+        mean_o[i] = mu;
+        rstd_o[i] = 1.0f / sqrtf(var + 1e-5f);
+      }
+      // (3) normalise and store: the statistics of row r sit in lanes 2r and 2r+1 of the lane's own half
+      const f32x4 g4 = *reinterpret_cast<const f32x4*>(ep.g + n), b4 = *reinterpret_cast<const f32x4*>(ep.b + n);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const size_t ob = (size_t)(m0 + wm * 64 + i * 32 + half * 4) * kDT + n;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float mu = __shfl(mean_o[i], (half << 5) | (2 * r), 64), rs = __shfl(rstd_o[i], (half << 5) | (2 * r), 64);
           f32x4 v = {acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]};
-          const size_t o = ob + (size_t)(qd * 8 + e4) * Nn;
-          if constexpr (EPI == kEpiAffineGeluF32) {
+          v = (v - mu) * rs * g4 + b4;
+          const size_t o = ob + (size_t)((r >> 2) * 8 + (r & 3)) * kDT;
+          PKV_ST(reinterpret_cast<f32x4*>(ep.out_f32 + o), v);
+          PKV_ST(reinterpret_cast<f16x4*>(ep.out_h + o), __builtin_convertvector(v, f16x4));
+        }
+      }
+      __syncthreads();  // the stage may be overwritten again
+    } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = gelu_erf(__builtin_fmaf(v[e], p0[e], p1[e]));
-            PKV_ST(reinterpret_cast<f32x4*>(ep.out_f32 + o), v);
-          } else if constexpr (EPI == kEpiBiasH) {
-            PKV_ST(reinterpret_cast<f16x4*>(ep.out_h + o), __builtin_convertvector(v + p0, f16x4));
-          } else if constexpr (EPI == kEpiBiasReluH) {
-            v += p0;
+      for (int i = 0; i < 2; ++i) {
+        if constexpr (EPI == kEpiQkvH) {
+          if (n0 >= 2 * kDT) {
+            // v: element (token m, column vc) goes to vt[(window * heads + head) * 64 + dd][pos]; the lane's eight tokens
+            // of a 16-token group (rows r = 8u .. 8u+7 of the tile pair qd = 2u, 2u+1) land in positions half*8 .. +7
+            const int vc = n - 2 * kDT;  // columns vc .. vc+3: one head, dd .. dd+3
+            const int mg = m0 + wm * 64 + i * 32;
+            uint16_t* vb = ep.out_v + ((size_t)((mg / kWin) * kHeads + (vc >> 6)) * 64 + (vc & 63)) * kWin + (mg % kWin) + half * 8;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaxf(v[e], 0.0f);
-            PKV_ST(reinterpret_cast<f16x4*>(ep.out_h + o), __builtin_convertvector(v, f16x4));
-          } else {
-            PKV_ST(reinterpret_cast<f32x4*>(ep.out_f32 + o), v + p0);
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+              for (int jn = 0; jn < 4; ++jn) {
+                f32x8 t;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) t[e] = acc[i][jn][u * 8 + e] + p0[jn];
+                PKV_ST(reinterpret_cast<f16x8*>(vb + (size_t)jn * kWin + u * 16), __builtin_convertvector(t, f16x8));
+              }
+            continue;
+          }
+        }
+        const size_t ob = (size_t)(m0 + wm * 64 + i * 32 + half * 4) * ep.ldc + n;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+#pragma unroll
+          for (int e4 = 0; e4 < 4; ++e4) {
+            const int r = qd * 4 + e4;
+            f32x4 v = {acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]};
+            const size_t o = ob + (size_t)(qd * 8 + e4) * ep.ldc;
+            if constexpr (EPI == kEpiAffineGeluF32) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] = gelu_erf(__builtin_fmaf(v[e], p0[e], p1[e]));
+              PKV_ST(reinterpret_cast<f32x4*>(ep.out_f32 + o), v);
+            } else if constexpr (EPI == kEpiQkvH) {
+              PKV_ST(reinterpret_cast<f16x4*>(ep.out_h + o), __builtin_convertvector(v + p0, f16x4));
+            } else if constexpr (EPI == kEpiBiasReluH) {
+              v += p0;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaxf(v[e], 0.0f);
+              PKV_ST(reinterpret_cast<f16x4*>(ep.out_h + o), __builtin_convertvector(v, f16x4));
+            } else {
+              PKV_ST(reinterpret_cast<f32x4*>(ep.out_f32 + o), v + p0);
+            }
           }
         }
       }
     }
     zero_acc();
     load_bias(s / nk + 1);
-  }
-}
-
-// ------------------------------------------------------------------------------------------
-// vt[window][head][dd][pos] = v of window row (window, p), taken from columns [2*d_time, 3*d_time) of the
-// QKV GEMM's output; pos = p with bits 2 and 3 of its offset inside a 16-token group swapped, which is
-// the order the P*V MFMA of the attention kernel consumes keys in.  A 64-token block with at least one row
-// below T is written whole (rows at and past T repeat row T-1: finite values under a zero probability).
-// grid (win / 64, heads, n_win), 256 threads: a 64 token x 64 dd tile goes through LDS.
-// ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void v_transpose_kernel(const uint16_t* __restrict__ qkv, uint16_t* __restrict__ vt,
-                                                           int64_t T) {
-  __shared__ uint16_t tile[64][64 + 2];
-  const int hd = blockIdx.y, wk = blockIdx.z, p0 = blockIdx.x * 64, tid = threadIdx.x;
-  const int64_t base = (int64_t)wk * kWin + p0;
-  if (base >= T) return;  // the attention kernel reads whole 64-token blocks up to the window's last token
-  {  // 64 rows x 8 chunks of 16 bytes = 512 chunks, two per thread
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int id = tid + 256 * i, row = id >> 3, ch = id & 7;
-      int64_t r = base + row;
-      r = r < T ? r : T - 1;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(qkv + (size_t)r * (3 * kDT) + 2 * kDT + hd * 64 + ch * 8);
-      uint32_t* d = reinterpret_cast<uint32_t*>(&tile[row][ch * 8]);
-      d[0] = v[0];
-      d[1] = v[1];
-      d[2] = v[2];
-      d[3] = v[3];
-    }
-  }
-  __syncthreads();
-  // thread writes 16 bytes = 8 consecutive positions of one dd row: positions q0 .. q0+7 of a 16-group are
-  // tokens with bits 2 and 3 swapped
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int id = tid + 256 * i, dd = id >> 3, q0 = (id & 7) * 8;
-    uint16_t o[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int pos = q0 + e, w16 = pos & 15;
-      const int tok = (pos & ~15) | (w16 & 3) | ((w16 & 4) << 1) | ((w16 & 8) >> 1);
-      o[e] = tile[tok][dd];
-    }
-    u32x4 pk;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) pk[e] = (uint32_t)o[2 * e] | ((uint32_t)o[2 * e + 1] << 16);
-    *reinterpret_cast<u32x4*>(vt + ((size_t)(wk * kHeads + hd) * 64 + dd) * kWin + p0 + q0) = pk;
   }
 }
 
@@ -350,43 +464,9 @@ __global__ __launch_bounds__(256) void gather_pe_kernel(const float* __restrict_
 }
 
 // ------------------------------------------------------------------------------------------
-// Post-norm residual step over rows of 512 (eps 1e-5): x = LN(x + in) * g + b, plus an fp16 copy.  One
-// wave per row.  The residual is added here and not in the producing GEMM's epilogue, where the loads
-// would stall the matrix pipe.
-// ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict__ in, const float* __restrict__ g,
-                                                         const float* __restrict__ b, float* __restrict__ x,
-                                                         uint16_t* __restrict__ xb, int64_t T) {
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= T) return;
-  const int lane = threadIdx.x & 63;
-  const float* src = in + (size_t)row * kDT;
-  f32x4 v0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + lane * 4));
-  f32x4 v1 = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + 256 + lane * 4));
-  v0 += *reinterpret_cast<const f32x4*>(x + (size_t)row * kDT + lane * 4);
-  v1 += *reinterpret_cast<const f32x4*>(x + (size_t)row * kDT + 256 + lane * 4);
-  float s = (v0[0] + v0[1]) + (v0[2] + v0[3]) + (v1[0] + v1[1]) + (v1[2] + v1[3]);
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
-  const float mu = s * (1.0f / kDT);
-  v0 -= mu;
-  v1 -= mu;
-  float q = (v0[0] * v0[0] + v0[1] * v0[1]) + (v0[2] * v0[2] + v0[3] * v0[3]) + (v1[0] * v1[0] + v1[1] * v1[1]) +
-            (v1[2] * v1[2] + v1[3] * v1[3]);
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) q += __shfl_xor(q, off, 64);
-  const float rstd = 1.0f / sqrtf(q * (1.0f / kDT) + 1e-5f);
-  const f32x4 g0 = *reinterpret_cast<const f32x4*>(g + lane * 4), g1 = *reinterpret_cast<const f32x4*>(g + 256 + lane * 4);
-  const f32x4 b0 = *reinterpret_cast<const f32x4*>(b + lane * 4), b1 = *reinterpret_cast<const f32x4*>(b + 256 + lane * 4);
-  const f32x4 y0 = v0 * rstd * g0 + b0, y1 = v1 * rstd * g1 + b1;
-  *reinterpret_cast<f32x4*>(x + (size_t)row * kDT + lane * 4) = y0;
-  *reinterpret_cast<f32x4*>(x + (size_t)row * kDT + 256 + lane * 4) = y1;
-  *reinterpret_cast<f16x4*>(xb + (size_t)row * kDT + lane * 4) = __builtin_convertvector(y0, f16x4);
-  *reinterpret_cast<f16x4*>(xb + (size_t)row * kDT + 256 + lane * 4) = __builtin_convertvector(y1, f16x4);
-}
-
-// ------------------------------------------------------------------------------------------
 // Window attention (8 heads x 64, full bidirectional attention inside each window).
+// qk [T, 2 * d_time] holds q then k of every window row; vt [window][head][64][win] holds v transposed, the keys of
+// every 16-group in the order the second product consumes them (both written by the QKV GEMM's epilogue).
 // Computes S^T = K Q^T so that a lane owns one query column; P^T then feeds the second MFMA as its
 // B operand straight from the accumulator registers, with V^T tiles as the A operand.
 // 256 threads; a workgroup owns 256 queries of one (window, head), a wave 64 of them (two 32-column
@@ -434,7 +514,7 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
     const int row = qi[cs] < len ? qi[cs] : len - 1;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
-      bq[cs][kk] = as_f16x8(*reinterpret_cast<const u32x4*>(qk + (size_t)(base + row) * (3 * kDT) + hd * 64 + kk * 16 + half * 8));
+      bq[cs][kk] = as_f16x8(*reinterpret_cast<const u32x4*>(qk + (size_t)(base + row) * (2 * kDT) + hd * 64 + kk * 16 + half * 8));
   }
   f32x16 o[2][2];  // [d half][query sub-tile]
 #pragma unroll
@@ -443,7 +523,7 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
     for (int cs = 0; cs < 2; ++cs) o[ds][cs] = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   float m_run[2] = {-1.0e30f, -1.0e30f}, l_run[2] = {0.0f, 0.0f};
 
-  const uint16_t* kbase = qk + (size_t)base * (3 * kDT) + kDT + hd * 64;
+  const uint16_t* kbase = qk + (size_t)base * (2 * kDT) + kDT + hd * 64;
   const uint16_t* vbase = vt + (size_t)(wk * kHeads + hd) * 64 * kWin;
   const int n_tiles = (len + 63) / 64;
   // staging: thread moves chunk tid % 8 of rows tid / 8 and tid / 8 + 32 of both tiles
@@ -457,7 +537,7 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
       const int row = srow + 32 * i;
       int j = j0 + row;
       j = j < len ? j : len - 1;
-      rk[i] = *reinterpret_cast<const u32x4*>(kbase + (size_t)j * (3 * kDT) + sch * 8);
+      rk[i] = *reinterpret_cast<const u32x4*>(kbase + (size_t)j * (2 * kDT) + sch * 8);
       rv[i] = *reinterpret_cast<const u32x4*>(vbase + (size_t)row * kWin + j0 + sch * 8);
     }
   };
@@ -669,26 +749,25 @@ __global__ __launch_bounds__(256) void stage3_kernel(const float* __restrict__ k
   for (int ll = ll_lo; ll < ll_hi; ++ll) yhat[((size_t)ll * H_l + h) * N + t] = y;
 }
 
-constexpr int kGemmLdsBytes = 2 * kGemmStageU4 * 16;
-
-template <int EPI>
+template <int EPI, int BM, int BN>
 hipError_t launch_gemm(const uint16_t* A, int lda, const uint16_t* W, int64_t M, int Nn, int K, const EpiArgs& ep,
                        int n_cu, hipStream_t stream) {
+  constexpr int kLdsBytes = 2 * (BM + BN) * (kGemmBK / 8) * 16;
   static bool attr_set = false;  // per instantiation; setting it again is harmless
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f16_kernel<EPI>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_f16_kernel<EPI, BM, BN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  if (Nn % kGemmBN != 0 || K % kGemmBK != 0 || M <= 0) return hipErrorInvalidValue;
-  const int m_tiles = (int)((M + kGemmBM - 1) / kGemmBM), n_tiles = Nn / kGemmBN;
+  if (Nn % BN != 0 || K % kGemmBK != 0 || M <= 0) return hipErrorInvalidValue;
+  const int m_tiles = (int)((M + BM - 1) / BM), n_tiles = Nn / BN;
   // one workgroup per CU, a multiple of the XCD count, no more than there are tiles per XCD list
   const int per_xcd_tiles = ((m_tiles + kXcds - 1) / kXcds) * n_tiles;
   int wg_per_xcd = n_cu / kXcds;
   if (wg_per_xcd < 1) wg_per_xcd = 1;
   if (wg_per_xcd > per_xcd_tiles) wg_per_xcd = per_xcd_tiles;
-  gemm_f16_kernel<EPI><<<kXcds * wg_per_xcd, 512, kGemmLdsBytes, stream>>>(A, lda, W, (int)M, Nn, K, ep);
+  gemm_f16_kernel<EPI, BM, BN><<<kXcds * wg_per_xcd, 512, kLdsBytes, stream>>>(A, lda, W, (int)M, Nn, K, ep);
   return hipGetLastError();
 }
 
@@ -716,49 +795,76 @@ hipError_t mapper_layer(proxykv_ctx* ctx, MapperWorkspace& m, const float* xl, i
   uint16_t* qk = (uint16_t*)m.qk.ptr;
   uint16_t* vt = (uint16_t*)m.vt.ptr;
   uint16_t* ao = (uint16_t*)m.ao.ptr;
-  float* tmp = (float*)m.tmp.ptr;
   uint16_t* hid = (uint16_t*)m.hid.ptr;
   uint16_t* zg = (uint16_t*)m.zg.ptr;
   float* kv3 = (float*)m.kv3.ptr;
+  uint32_t* range = (uint32_t*)m.range.ptr;
   const unsigned ew_blocks_T = (unsigned)((T * (kDT / 4) + 255) / 256);
   const unsigned ew_blocks_N = (unsigned)((N * (kDT / 4) + 255) / 256);
 
   // stage 1
-  stem_conv1_kernel<<<(unsigned)((N + kStemTok - 1) / kStemTok), 256, 0, stream>>>(xl, w.conv1_w, w.bn1_scale, w.bn1_shift, h1,
-                                                                                  c.H_kv, (int)N, c.c_mid);
+  {
+    const int64_t n_x = (int64_t)c.H_kv * N;
+    const unsigned blocks = (unsigned)((n_x + 256 * 16 - 1) / (256 * 16) < 1024 ? (n_x + 256 * 16 - 1) / (256 * 16) : 1024);
+    absmax_kernel<<<blocks, 256, 0, stream>>>(xl, n_x, range);
+    PKV_TRY(hipGetLastError());
+    stem_scale_kernel<<<1, 64, 0, stream>>>(range, w.stem_cw, w.stem_cs);
+    PKV_TRY(hipGetLastError());
+  }
+  stem_conv1_kernel<<<(unsigned)((N + kStemTok - 1) / kStemTok), 256, 0, stream>>>(
+      xl, w.conv1_w, w.bn1_scale, w.bn1_shift, reinterpret_cast<const float*>(range), h1, c.H_kv, (int)N, c.c_mid);
   PKV_TRY(hipGetLastError());
-  EpiArgs e2 = {w.bn2_scale, w.bn2_shift, z_local, nullptr};
-  PKV_TRY(launch_gemm<kEpiAffineGeluF32>(h1, c.c_mid, w.conv2_w, N, kDT, 3 * c.c_mid, e2, n_cu, stream));
+  EpiArgs e2 = {};
+  e2.p0 = w.bn2_scale;
+  e2.p1 = w.bn2_shift;
+  e2.p2 = reinterpret_cast<const float*>(range) + 2;
+  e2.out_f32 = z_local;
+  e2.ldc = kDT;
+  PKV_TRY((launch_gemm<kEpiAffineGeluF32, 256, 256>(h1, c.c_mid, w.conv2_w, N, kDT, 3 * c.c_mid, e2, n_cu, stream)));
 
   // stage 2
   gather_pe_kernel<<<ew_blocks_T, 256, 0, stream>>>(z_local, w.pe, x, xb, T);
   PKV_TRY(hipGetLastError());
   for (int li = 0; li < c.n_enc_layers; ++li) {
     const EncoderLayerWeights& e = w.enc[li];
-    EpiArgs eq = {e.in_b, nullptr, nullptr, qk};
-    PKV_TRY(launch_gemm<kEpiBiasH>(xb, kDT, e.in_w, T, 3 * kDT, kDT, eq, n_cu, stream));
-    v_transpose_kernel<<<dim3(kWin / 64, kHeads, (unsigned)n_win), 256, 0, stream>>>(qk, vt, T);
-    PKV_TRY(hipGetLastError());
+    EpiArgs eq = {};
+    eq.p0 = e.in_b;
+    eq.out_h = qk;
+    eq.out_v = vt;
+    eq.ldc = 2 * kDT;
+    PKV_TRY((launch_gemm<kEpiQkvH, 256, 256>(xb, kDT, e.in_w, T, 3 * kDT, kDT, eq, n_cu, stream)));
     window_attention_kernel<<<(unsigned)(n_win * kHeads * (kWin / 256)), 256, 0, stream>>>(qk, vt, ao, T, (int)n_win);
     PKV_TRY(hipGetLastError());
-    EpiArgs eo = {e.out_b, nullptr, tmp, nullptr};
-    PKV_TRY(launch_gemm<kEpiBiasF32>(ao, kDT, e.out_w, T, kDT, kDT, eo, n_cu, stream));
-    layernorm_kernel<<<(unsigned)((T + 3) / 4), 256, 0, stream>>>(tmp, e.ln1_g, e.ln1_b, x, xb, T);
-    PKV_TRY(hipGetLastError());
-    EpiArgs e1 = {e.ffn1_b, nullptr, nullptr, hid};
-    PKV_TRY(launch_gemm<kEpiBiasReluH>(xb, kDT, e.ffn1_w, T, c.d_ffn, kDT, e1, n_cu, stream));
-    EpiArgs ef = {e.ffn2_b, nullptr, tmp, nullptr};
-    PKV_TRY(launch_gemm<kEpiBiasF32>(hid, c.d_ffn, e.ffn2_w, T, kDT, c.d_ffn, ef, n_cu, stream));
-    layernorm_kernel<<<(unsigned)((T + 3) / 4), 256, 0, stream>>>(tmp, e.ln2_g, e.ln2_b, x, xb, T);
-    PKV_TRY(hipGetLastError());
+    EpiArgs eo = {};
+    eo.p0 = e.out_b;
+    eo.g = e.ln1_g;
+    eo.b = e.ln1_b;
+    eo.res = x;
+    eo.out_f32 = x;
+    eo.out_h = xb;
+    eo.ldc = kDT;
+    PKV_TRY((launch_gemm<kEpiResLn, 128, 512>(ao, kDT, e.out_w, T, kDT, kDT, eo, n_cu, stream)));
+    EpiArgs e1 = {};
+    e1.p0 = e.ffn1_b;
+    e1.out_h = hid;
+    e1.ldc = c.d_ffn;
+    PKV_TRY((launch_gemm<kEpiBiasReluH, 256, 256>(xb, kDT, e.ffn1_w, T, c.d_ffn, kDT, e1, n_cu, stream)));
+    EpiArgs ef = eo;
+    ef.p0 = e.ffn2_b;
+    ef.g = e.ln2_g;
+    ef.b = e.ln2_b;
+    PKV_TRY((launch_gemm<kEpiResLn, 128, 512>(hid, c.d_ffn, e.ffn2_w, T, kDT, c.d_ffn, ef, n_cu, stream)));
   }
   overlap_avg_kernel<<<ew_blocks_N, 256, 0, stream>>>(x, zg, N, (int)n_win);
   PKV_TRY(hipGetLastError());
 
   // stage 3
   const int nkv = kv3_stride(c);
-  EpiArgs e3 = {w.kv_b, nullptr, kv3, nullptr};
-  PKV_TRY(launch_gemm<kEpiBiasF32>(zg, kDT, w.kv_w, N, nkv, kDT, e3, n_cu, stream));
+  EpiArgs e3 = {};
+  e3.p0 = w.kv_b;
+  e3.out_f32 = kv3;
+  e3.ldc = nkv;
+  PKV_TRY((launch_gemm<kEpiBiasF32, 256, 256>(zg, kDT, w.kv_w, N, nkv, kDT, e3, n_cu, stream)));
   const int tok_per_block = 256 / c.H_l;
   stage3_kernel<<<(unsigned)((N + tok_per_block - 1) / tok_per_block), 256, 0, stream>>>(kv3, w.queries, w.out_w, w.out_b, yhat, N,
                                                                                         c.H_kv, c.H_l, nkv, ll, ll_hi);

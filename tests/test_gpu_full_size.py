@@ -253,6 +253,33 @@ def test_llama_8k_sum_form_full_size():
     pk.proxykv_destroy(ctx)
 
 
+def test_llama_8k_sum_form_score_then_map_against_the_oracle():
+    """The feature in the form Sec. 3 prints (sum over the query axis) feeding the mapper of Sec. 4.1 at full size:
+    proxykv_score (reduce = SUM) then proxykv_map on the GPU, against the oracle's own scores of the sampled proxy
+    layers' eight KV heads pushed through the oracle's mapper on sampled spans.  No oracle input comes from the GPU."""
+    case = synth.CASES["llama_8k"]
+    w = synth.make_mapper_weights(case.H_kv, case.H_l)
+    cfg = pk.config_for_case(case)
+    cfg.reduce = pk.PROXYKV_REDUCE_SUM
+    ctx = pk.proxykv_create(cfg)
+    pk.proxykv_set_mapper_weights(ctx, w)
+    q, kc, kr = synth.make_proxy_qk(case, device="cuda")
+    x = pk.proxykv_score(ctx, q, kc, kr, case.chunk)
+    y = pk.proxykv_map(ctx, x)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(y).all())
+    pairing = pk.proxykv_layer_pairing(ctx.cfg)
+    G = case.G
+    for (ls, a, b) in ((3, 0, 1024), (12, case.N - 1024, case.N)):
+        X_l = torch.stack([oracle.score_unit(q[ls, h * G:(h + 1) * G].double().cpu(), kc[ls, h].double().cpu(),
+                                             kr[ls, h].double().cpu(), case.chunk, reduce="sum") for h in range(case.H_kv)])
+        _close(x[ls], X_l, f"score sum[llama_8k] proxy layer {ls}")
+        ref = _oracle_span(X_l, w, a, b)
+        for ll in [t for t in range(case.L_l) if pairing[t] == ls]:
+            _close(y[ll, :, a:b], ref, f"sum-form score -> map[llama_8k] proxy layer {ls} -> target layer {ll}, tokens [{a}, {b})")
+    pk.proxykv_destroy(ctx)
+
+
 def test_llama_8k_score_self_full_size():
     """The causal self-attention feature at full size: one whole (layer, KV head) unit key by key against the oracle;
     on every unit the total over the keys equals the number of query rows (every row is a probability vector), the

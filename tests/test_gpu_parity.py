@@ -351,6 +351,34 @@ def test_mapper_degenerate_lengths(N):
     pk.proxykv_destroy(ctx)
 
 
+def test_mapper_with_scores_beyond_the_half_range():
+    """Sum-form scores with an attention sink (Sec. 3 prints the feature as a sum over the query axis, so one key can
+    collect a share of every row): the first conv block's output reaches 1.4e5, beyond what IEEE half holds.  The
+    library stores that operand as a half value times a power of two taken from the layer's largest score; the oracle
+    rounds it to an 11-bit significand without a range limit.  Also the same mapper on ordinary scores right after
+    (the range exponent is per call and per layer)."""
+    case = synth.scaled_case(synth.CASES["llama_8k"], name="sink", L_s=2, H_kv=2, H_q=2, L_l=2, H_l=4, N=700, N_q=1, chunk=1,
+                             n_planted=0)
+    w = synth.make_mapper_weights(case.H_kv, case.H_l)
+    g = torch.Generator().manual_seed(5)
+    X = (torch.rand(case.L_s, case.H_kv, case.N, generator=g) * 8).to(torch.float32)
+    X[0, :, 0] = 1.0e5                                   # layer 0: a sink at the first token and a smaller one mid-way
+    X[0, :, 350] = 3.0e4
+    ref = oracle.mapper(X, w, case.L_l)
+    assert bool(torch.isfinite(ref).all())
+    a1 = torch.nn.functional.conv1d(X[0:1].double(), w["stem.conv1.weight"].double(), w["stem.conv1.bias"].double(), padding=1)
+    assert float(a1.abs().max()) > 65504.0                # the case does leave half's range
+    ctx = _ctx(case, w)
+    y = pk.proxykv_map(ctx, X.cuda())
+    torch.cuda.synchronize()
+    assert_close(y, ref, "map with a sink")
+    X2 = (torch.rand(case.L_s, case.H_kv, case.N, generator=g) ** 8).to(torch.float32)
+    y2 = pk.proxykv_map(ctx, X2.cuda())
+    torch.cuda.synchronize()
+    assert_close(y2, oracle.mapper(X2, w, case.L_l), "map after a sink")
+    pk.proxykv_destroy(ctx)
+
+
 def test_mapper_context_reuse_across_lengths():
     """One context called with a short, a longer and again a shorter sequence (the workspace of every lane grows in
     between; three distinct proxy layers run side by side): same bits as a fresh context each time, and the oracle's
