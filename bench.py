@@ -20,6 +20,22 @@ def flops_score(case):
     return per_pair * (case.N_q * case.N + tri), per_pair * case.N_q * case.N
 
 
+def flops_map(case):
+    """Algorithmic flops of the mapper (Sec. 4.1) with the network run once per distinct proxy layer: per window row
+    the four linear maps and the FFN of every encoder layer (2 flop per multiply-add), the attention of every window
+    (QK^T and PV over the window's own length), the second stem convolution and the stage-3 key/value projection.
+    The first convolution and the per-token stage-3 attention run on the vector ALU and are left out."""
+    d_time, c_mid, n_layers, d_ffn, d_head, win, stride = 512, 256, 6, 2048, 64, 2048, 1024
+    N = case.N
+    n_win = 1 if N <= win else -((-(N - win)) // stride) + 1
+    lens = [min(k * stride + win, N) - k * stride for k in range(n_win)]
+    rows = sum(lens)
+    per_layer = n_layers * (2 * rows * (4 * d_time * d_time + 2 * d_time * d_ffn) + sum(4 * l * l * d_time for l in lens))
+    per_layer += 2 * N * 3 * c_mid * d_time + 2 * N * d_time * 2 * case.H_kv * d_head
+    distinct = len({-((-(ll * case.L_s)) // case.L_l) for ll in range(1, case.L_l + 1)})
+    return per_layer * distinct
+
+
 def bytes_topk_compact(case, K):
     rows = case.L_l * case.H_l
     topk = rows * (4 * case.N + 4 * K)
@@ -28,15 +44,17 @@ def bytes_topk_compact(case, K):
 
 
 def measured_traffic(workload, kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this workload
-    (two --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by a 1 GiB copy); None if there is none."""
+    """HBM bytes per launch of `kernel` as the committed rocprofv3 counter summary of this workload gives them (two
+    --pmc runs, FETCH_SIZE and WRITE_SIZE, scaled by a 1 GiB copy), with the file it was read from; (None, None) if
+    there is none.  A stored figure of an earlier profiling run, not a measurement of the run that prints it."""
     import os
     import re
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"prune_{workload}_hbm_counters.md")
+    rel = os.path.join("profiles", f"prune_{workload}_hbm_counters.md")
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), rel)
     if not os.path.exists(path):
-        return None
+        return None, None
     m = re.search(r"traffic_bytes_per_launch\[%s_kernel\] = ([0-9.eE+-]+)" % re.escape(kernel), open(path).read())
-    return float(m.group(1)) if m else None
+    return (float(m.group(1)), rel) if m else (None, None)
 
 
 def cpu_baseline(case, keep_ratio, x_layer0):
@@ -174,17 +192,23 @@ def main():
     dominant = max(kern, key=lambda s: stage_ms[s])
     peak_tflops = 2500.0
     achieved = kern[dominant] / (stage_ms[dominant] * 1e-3) / 1e12
+    traffic, traffic_from = measured_traffic(case.name, dominant)
+    f_map = flops_map(case)
+    map_tflops = f_map / (stage_ms["map"] * 1e-3) / 1e12
     b_topk, b_comp = bytes_topk_compact(case, K)
     hbm_gbps = (b_topk + b_comp) / ((stage_ms["topk"] + stage_ms["compact"]) * 1e-3) / 1e9
     out = {
         "metric": "scored context tokens/s (score+map+TopK+compact)",
         "value": case.N / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16 score / fp16 mapper operands, fp32 accumulate", "data": "synthetic",
         "config": {"workload": case.name, "reduce": args.reduce, "N": case.N, "N_q": case.N_q, "chunk": case.chunk, "keep_ratio": args.keep_ratio,
                    "K": K, "proxy": [case.L_s, case.H_q, case.H_kv, case.d], "target": [case.L_l, case.H_l, case.D]},
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": achieved, "peak": peak_tflops, "unit": "TFLOP/s",
-                     "frac": achieved / peak_tflops, "traffic": measured_traffic(case.name, dominant)},
+                     "frac": achieved / peak_tflops, "traffic": traffic, "traffic_from": traffic_from},
+        # the mapper as a whole (GEMMs and window attention on fp16 MFMA, fp32 accumulate) against the same matrix peak
+        "roofline_map": {"bound": "mfma", "kernel": "mapper (all kernels of the stage)", "achieved": map_tflops, "peak": peak_tflops,
+                         "unit": "TFLOP/s", "frac": map_tflops / peak_tflops, "flop": f_map},
         # pass 1 seen from the vector ALU, which is what bounds it: per visited pair one fma (2 flop), one exp2, one add
         # = 4 flop in 4 issue slots of a lane (exp2 runs at half rate); 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz slots/s
         "roofline_alu": {"bound": "alu", "kernel": "score_lse", "achieved": 4 * f_lse / (2 * case.d) / (stage_ms["score_lse"] * 1e-3) / 1e12,
