@@ -163,8 +163,8 @@ int proxykv_topk(proxykv_ctx* ctx, const float* scores, int64_t rows, int64_t N,
  * workspace growth): the per-row histograms and counters that rows longer than 36 864 scores need live in a fixed
  * array of 8 MiB inside the library's device image (every GPU the library runs on holds it until the process ends).
  * Rows of up to 36 864 scores need none of it.  For longer rows the call needs
- *     rows * (1040 + 257 * ceil(N / 36864)) * 4 bytes <= proxykv_topk_static_limit() = 8 MiB
- * (901 rows of 170 000 scores, 677 of 262 144) and returns PROXYKV_ELIMIT beyond that, before any device work.
+ *     rows * (1040 + 257 * ceil(N / 45056)) * 4 bytes <= proxykv_topk_static_limit() = 8 MiB
+ * (1014 rows of 170 000 scores, 812 of 262 144) and returns PROXYKV_ELIMIT beyond that, before any device work.
  * All calls on one GPU share the array: calls that overlap in time on one GPU (different streams or contexts) race;
  * calls on one stream are ordered and each clears what it needs with a kernel of its own (no memset node, so the
  * call can be captured).  The first call on a device looks up the array's address (the runtime loads the device

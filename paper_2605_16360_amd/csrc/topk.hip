@@ -103,7 +103,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float* __r
   const float* row = scores + (size_t)blockIdx.x * N;
   int32_t* out = idx_out + (size_t)blockIdx.x * K;
   __shared__ uint32_t hist[kTopkWaves][256];
-  __shared__ uint32_t tot[256];
+  __shared__ uint32_t tot[2][256];
   __shared__ uint32_t s_prefix, s_krem;
   __shared__ uint32_t wave_a[kTopkWaves], wave_b[kTopkWaves];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -126,6 +126,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float* __r
   }
   const int mine = N - i0 < 0 ? 0 : (N - i0 < kTopkItems ? N - i0 : kTopkItems);  // valid items of this thread
 
+  // the first pass's histograms (one per wave) are cleared under the barrier of the range reduction
+  for (int i = tid; i < kTopkWaves * 256; i += kTopkThreads) (&hist[0][0])[i] = 0;
   uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
   for (int j = 0; j < kTopkItems; ++j) {
@@ -153,28 +155,37 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float* __r
   const uint32_t span = kmax - kmin;
   int prev_sh = span == 0 ? 0 : 32 - __builtin_clz(span);
 
+  // Pass p counts into tot[p & 1].  First pass: every key counts, one histogram per wave keeps lanes of different waves
+  // off the same counter, and their sum goes to tot[0].  Later passes: only the keys under the prefix (a 256th of the
+  // row per pass) count, straight into tot[p & 1], which was cleared while the pass before picked its digit.
   uint32_t prefix = 0, krem = (uint32_t)K;
-  bool first = true;
+  int pass = 0;
   while (prev_sh > 0) {
     const int shift = prev_sh > 8 ? prev_sh - 8 : 0;
     const uint32_t dmask = (1u << (prev_sh - shift)) - 1u;
-    for (int i = tid; i < kTopkWaves * 256; i += kTopkThreads) (&hist[0][0])[i] = 0;
-    __syncthreads();
+    uint32_t* cur = tot[pass & 1];
+    if (pass == 0) {
 #pragma unroll
-    for (int j = 0; j < kTopkItems; ++j) {
-      const uint32_t rel = key[j] - kmin;
-      if (j < mine && (first || (rel >> prev_sh) == prefix)) atomicAdd(&hist[wave][(rel >> shift) & dmask], 1u);
+      for (int j = 0; j < kTopkItems; ++j)
+        if (j < mine) atomicAdd(&hist[wave][((key[j] - kmin) >> shift) & dmask], 1u);
+      __syncthreads();
+      if (tid < 256) {
+        uint32_t sum = 0;
+#pragma unroll
+        for (int w = 0; w < kTopkWaves; ++w) sum += hist[w][tid];
+        cur[tid] = sum;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < kTopkItems; ++j) {
+        const uint32_t rel = key[j] - kmin;
+        if (j < mine && (rel >> prev_sh) == prefix) atomicAdd(&cur[(rel >> shift) & dmask], 1u);
+      }
     }
     __syncthreads();
-    if (tid < 256) {
-      uint32_t sum = 0;
-#pragma unroll
-      for (int w = 0; w < kTopkWaves; ++w) sum += hist[w][tid];
-      tot[tid] = sum;
-    }
-    __syncthreads();
+    if (tid < 256) tot[(pass + 1) & 1][tid] = 0;
     if (wave == 0) {
-      const uint32_t c0 = tot[4 * lane], c1 = tot[4 * lane + 1], c2 = tot[4 * lane + 2], c3 = tot[4 * lane + 3];
+      const uint32_t c0 = cur[4 * lane], c1 = cur[4 * lane + 1], c2 = cur[4 * lane + 2], c3 = cur[4 * lane + 3];
       const uint32_t own = c0 + c1 + c2 + c3;
       uint32_t v = own;
 #pragma unroll
@@ -197,11 +208,12 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float* __r
     prefix = s_prefix;
     krem = s_krem;
     prev_sh = shift;
-    first = false;
+    ++pass;
   }
   const uint32_t T = prefix + kmin, eq_take = krem;
 
-  // kept: keys above T, and the eq_take lowest-index keys equal to T
+  // kept: keys above T, and the eq_take lowest-index keys equal to T.  One prefix sum over the threads carries both
+  // counts (each at most 36 864, so 16 bits apiece): the kept equal keys before a thread are min(equal before, eq_take).
   uint32_t n_gt = 0, n_eq = 0;
 #pragma unroll
   for (int j = 0; j < kTopkItems; ++j) {
@@ -210,11 +222,12 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float* __r
       n_eq += key[j] == T;
     }
   }
-  uint32_t tot_eq, tot_gt;
-  const uint32_t eq_before = block_exclusive_scan(n_eq, wave_a, wave, lane, tot_eq);
-  const uint32_t eq_mine = eq_before >= eq_take ? 0u : (eq_take - eq_before < n_eq ? eq_take - eq_before : n_eq);
-  uint32_t pos = block_exclusive_scan(n_gt + eq_mine, wave_b, wave, lane, tot_gt);
-  uint32_t eq_left = eq_mine;
+  static_assert(kTopkRegMax < 65536, "two 16-bit counts share one prefix sum");
+  uint32_t both_total;
+  const uint32_t both = block_exclusive_scan((n_gt << 16) | n_eq, wave_a, wave, lane, both_total);
+  const uint32_t eq_before = both & 0xffffu, gt_before = both >> 16;
+  uint32_t pos = gt_before + (eq_before < eq_take ? eq_before : eq_take);
+  uint32_t eq_left = eq_before >= eq_take ? 0u : (eq_take - eq_before < n_eq ? eq_take - eq_before : n_eq);
 #pragma unroll
   for (int j = 0; j < kTopkItems; ++j) {
     if (j < mine) {
@@ -230,8 +243,9 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float* __r
 }
 
 // ---------------------------------------------------------------------------------------------
-// Rows longer than kTopkRegMax: part p of a row (thread t keeps the keys of the consecutive scores
-// [p * part_len + t * kTopkItems, + kTopkItems) in registers) is one workgroup.  Scratch memory per row (32-bit words):
+// Rows longer than kTopkRegMax are cut into parts of at most kMwPartMax = 45 056 scores (170 000 scores: four parts,
+// so that 112 rows are 448 workgroups, one round on 256 CUs); part p of a row (thread t keeps the keys of the
+// consecutive scores [p * part_len + t * kMwItems, + kMwItems) in registers) is one workgroup.  Scratch memory per row (32-bit words):
 //   [0, 16)                      state: prefix, krem, then one arrival counter per pass at [4 + pass]
 //   [16, 16 + 4 * 256)           the row's histogram of every pass
 //   [1040, 1040 + parts * 257)   per part: its histogram of the last pass (256), then its number of keys above the
@@ -241,6 +255,7 @@ __global__ __launch_bounds__(kTopkThreads) void topk_reg_kernel(const float* __r
 // far; the workgroup that arrives last at the row's counter has every part's contribution in the row's histogram
 // (each part adds its bins, fences, then takes its ticket) and picks the bin that holds the krem-th largest key.
 // ---------------------------------------------------------------------------------------------
+constexpr int kMwItems = 44, kMwPartMax = kMwItems * kTopkThreads;  // scores per thread and per part
 constexpr int kMwStateWords = 16, kMwRowFixedWords = kMwStateWords + 4 * 256, kMwPartWords = 257;
 
 __global__ void mw_init_kernel(uint32_t* __restrict__ scratch, int rows, int row_words, int K) {
@@ -251,13 +266,13 @@ __global__ void mw_init_kernel(uint32_t* __restrict__ scratch, int rows, int row
 }
 
 // keys of part `part` of the row in registers; positions at and past the part's end hold key 0 and are never counted
-__device__ __forceinline__ int mw_load_keys(const float* row, int N, int part_len, int part, int tid, uint32_t (&key)[kTopkItems],
+__device__ __forceinline__ int mw_load_keys(const float* row, int N, int part_len, int part, int tid, uint32_t (&key)[kMwItems],
                                             int& i0) {
   const int lo = part * part_len, hi = lo + part_len < N ? lo + part_len : N;
-  i0 = lo + tid * kTopkItems;
-  if ((reinterpret_cast<uintptr_t>(row + i0) & 15) == 0 && i0 + kTopkItems <= hi) {
+  i0 = lo + tid * kMwItems;
+  if ((reinterpret_cast<uintptr_t>(row + i0) & 15) == 0 && i0 + kMwItems <= hi) {
 #pragma unroll
-    for (int j = 0; j < kTopkItems; j += 4) {
+    for (int j = 0; j < kMwItems; j += 4) {
       const f32x4 v = *reinterpret_cast<const f32x4*>(row + i0 + j);
       key[j] = order_key(v[0]);
       key[j + 1] = order_key(v[1]);
@@ -266,9 +281,9 @@ __device__ __forceinline__ int mw_load_keys(const float* row, int N, int part_le
     }
   } else {
 #pragma unroll
-    for (int j = 0; j < kTopkItems; ++j) key[j] = i0 + j < hi ? order_key(row[i0 + j]) : 0u;
+    for (int j = 0; j < kMwItems; ++j) key[j] = i0 + j < hi ? order_key(row[i0 + j]) : 0u;
   }
-  return hi - i0 < 0 ? 0 : (hi - i0 < kTopkItems ? hi - i0 : kTopkItems);
+  return hi - i0 < 0 ? 0 : (hi - i0 < kMwItems ? hi - i0 : kMwItems);
 }
 
 // grid (parts, rows)
@@ -280,7 +295,7 @@ __global__ __launch_bounds__(kTopkThreads) void mw_pass_kernel(const float* __re
   __shared__ uint32_t hist[kTopkWaves][256];
   __shared__ uint32_t tot[256];
   __shared__ uint32_t s_last, wave_hi[kTopkWaves];
-  uint32_t key[kTopkItems];
+  uint32_t key[kMwItems];
   int i0;
   const int mine = mw_load_keys(row, N, part_len, part, tid, key, i0);
   const uint32_t prefix = rs[0];  // the bits above `shift + 8` of the K-th largest key (written by the previous launch)
@@ -289,7 +304,7 @@ __global__ __launch_bounds__(kTopkThreads) void mw_pass_kernel(const float* __re
   __syncthreads();
   uint32_t n_hi = 0;  // last pass: keys above the prefix
 #pragma unroll
-  for (int j = 0; j < kTopkItems; ++j) {
+  for (int j = 0; j < kMwItems; ++j) {
     const bool valid = j < mine;
     const bool match = valid && (pass == 0 || (key[j] >> (shift + 8)) == prefix);
     const uint32_t digit = (key[j] >> shift) & 255u;
@@ -327,14 +342,14 @@ __global__ __launch_bounds__(kTopkThreads) void mw_pass_kernel(const float* __re
       rs[kMwRowFixedWords + part * kMwPartWords + 256] = t;
     }
   }
-  // this part's bins are in the row's histogram before its ticket is taken
-  __threadfence();
+  // This part's bins are in the row's histogram before its ticket is taken: the adds are device-scope atomics, carried
+  // out where all workgroups meet, and the barrier lets no wave pass before its own adds have been acknowledged.  (A
+  // device-wide fence here instead costs a write-back of the whole L2 per workgroup: 200 us per launch at 560 groups.)
   __syncthreads();
   if (tid == 0) s_last = (atomicAdd(&rs[4 + pass], 1u) == (uint32_t)(parts - 1));
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
-  if (tid < 256) tot[tid] = atomicAdd(&rs[kMwStateWords + pass * 256 + tid], 0u);  // read at the L2, where the adds met
+  if (tid < 256) tot[tid] = atomicAdd(&rs[kMwStateWords + pass * 256 + tid], 0u);  // read where the adds met
   __syncthreads();
   if (wave == 0) {
     const uint32_t krem = rs[1];
@@ -370,7 +385,7 @@ __global__ __launch_bounds__(kTopkThreads) void mw_write_kernel(const float* __r
   const uint32_t* rs = scratch + (size_t)blockIdx.y * row_words;
   int32_t* out = idx_out + (size_t)blockIdx.y * K;
   __shared__ uint32_t wave_a[kTopkWaves], wave_b[kTopkWaves];
-  uint32_t key[kTopkItems];
+  uint32_t key[kMwItems];
   int i0;
   const int mine = mw_load_keys(row, N, part_len, part, tid, key, i0);
   const uint32_t T = rs[0], eq_take = rs[1], t8 = T & 255u;
@@ -391,7 +406,7 @@ __global__ __launch_bounds__(kTopkThreads) void mw_write_kernel(const float* __r
 
   uint32_t n_gt = 0, n_eq = 0;
 #pragma unroll
-  for (int j = 0; j < kTopkItems; ++j) {
+  for (int j = 0; j < kMwItems; ++j) {
     if (j < mine) {
       n_gt += key[j] > T;
       n_eq += key[j] == T;
@@ -404,7 +419,7 @@ __global__ __launch_bounds__(kTopkThreads) void mw_write_kernel(const float* __r
   uint32_t pos = part_pos + block_exclusive_scan(n_gt + eq_mine, wave_b, wave, lane, tot_kept);
   uint32_t eq_left = eq_mine;
 #pragma unroll
-  for (int j = 0; j < kTopkItems; ++j) {
+  for (int j = 0; j < kMwItems; ++j) {
     if (j < mine) {
       const bool take = key[j] > T || (key[j] == T && eq_left > 0);
       if (key[j] == T && eq_left > 0) --eq_left;
@@ -420,11 +435,12 @@ __global__ __launch_bounds__(kTopkThreads) void mw_write_kernel(const float* __r
 
 }  // namespace
 
-static int topk_parts(int64_t N) { return N <= kTopkRegMax ? 1 : (int)((N + kTopkRegMax - 1) / kTopkRegMax); }
+// parts of a row that is too long for one register-resident workgroup (may be one)
+static int topk_parts(int64_t N) { return (int)((N + kMwPartMax - 1) / kMwPartMax); }
 
 size_t topk_scratch_bytes(int64_t rows, int64_t N) {
+  if (N <= kTopkRegMax || rows <= 0) return 0;
   const int parts = topk_parts(N);
-  if (parts == 1 || rows <= 0) return 0;
   return (size_t)rows * (size_t)(kMwRowFixedWords + parts * kMwPartWords) * 4;
 }
 
@@ -434,7 +450,7 @@ static hipError_t launch_topk_impl(const float* scores, int64_t rows, int64_t N,
   if (rows <= 0) return hipSuccess;
   const GatherArgs none = {nullptr, nullptr, nullptr, nullptr, 0};
   const int parts = topk_parts(N);
-  if (parts == 1) {
+  if (N <= kTopkRegMax) {
     if (gather) topk_reg_kernel<true><<<dim3((unsigned)rows), kTopkThreads, 0, stream>>>(scores, (int)N, (int)K, idx_out, *gather);
     else topk_reg_kernel<false><<<dim3((unsigned)rows), kTopkThreads, 0, stream>>>(scores, (int)N, (int)K, idx_out, none);
     return hipGetLastError();

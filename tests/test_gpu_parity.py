@@ -58,10 +58,10 @@ def test_topk_bit_exact(N, K):
     assert torch.equal(got.cpu(), ref)
 
 
-@pytest.mark.parametrize("N", [36863, 36864, 36865, 40000, 73729, 170000])
+@pytest.mark.parametrize("N", [36863, 36864, 36865, 40000, 45057, 90113, 170000])
 def test_topk_bit_exact_around_the_kernel_switch(N):
-    """Rows of up to 36 864 scores are selected by one workgroup, longer ones are split over several (two parts, three
-    parts with a ragged last one, five parts)."""
+    """Rows of up to 36 864 scores are selected by one workgroup, longer ones are split into parts of at most 45 056
+    (one part, two parts, three parts with a ragged last one, four parts)."""
     ctx = _ctx(synth.CASES["tiny"])
     g = torch.Generator().manual_seed(N)
     s = torch.randn(5, N, generator=g)

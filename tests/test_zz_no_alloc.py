@@ -29,7 +29,7 @@ def test_topk_static_matches_topk_on_two_calls_in_a_row():
     assert lib.proxykv_topk_static(ctx.handle, warm.data_ptr(), 1, 8, 2, warm_idx.data_ptr(), None) == pk.PROXYKV_OK
     torch.cuda.synchronize()
     assert warm_idx.tolist() == [[0, 1]]
-    # long rows first (five parts per row: the scratch holds histograms and counters), then shorter rows with fewer
+    # long rows first (four parts per row: the scratch holds histograms and counters), then shorter rows with fewer
     # parts and a different K, then rows that need no scratch at all
     for (rows, N, K) in ((6, 170000, 51000), (4, 73729, 20000), (5, 32768, 9830)):
         s = _scores(rows, N, N)
@@ -53,7 +53,7 @@ def test_topk_static_rejects_what_does_not_fit_before_any_device_work():
     limit = pk.proxykv_topk_static_limit()
     assert limit == 8 << 20
     one = ctypes.c_void_p(16)                     # never dereferenced
-    rows = limit // ((1040 + 257 * 5) * 4) + 1    # one row too many at N = 170 000
+    rows = limit // ((1040 + 257 * 4) * 4) + 1    # one row too many at N = 170 000 (four parts per row)
     assert lib.proxykv_topk_static(ctx.handle, one, rows, 170000, 10, one, None) == pk.PROXYKV_ELIMIT
     assert lib.proxykv_topk_static(ctx.handle, one, 1, 8, 9, one, None) == pk.PROXYKV_EINVAL
     assert lib.proxykv_topk_static(ctx.handle, None, 1, 8, 2, one, None) == pk.PROXYKV_EINVAL
