@@ -50,15 +50,16 @@ struct MapperWeights {
 // Row length of the stage-3 K/V projection's output: 2*H_kv*d_head_x rounded up to the GEMM's column tile.
 inline int kv3_stride(const proxykv_config& c) { return (2 * c.H_kv * c.d_head_x + 255) / 256 * 256; }
 
-// Distinct proxy layers are independent, so several of them run side by side, each on a stream ("lane") and in a
+// Distinct proxy layers are independent, so kMapLanes of them run side by side, each on a stream ("lane") and in a
 // workspace of its own; lane 0 is the caller's stream.  Short contexts leave most of the chip idle inside one layer's
-// kernels (at N = 8192 a layer is 14 336 window rows: 112 output tiles for 256 CUs) and take kMapLanes lanes; long ones
-// take two, which lets one layer's bandwidth-bound kernels (layer norm, V transpose) run under the other's GEMMs and
-// attention (measured at N = 32 768: 91 ms against 97 ms with one lane, no further gain with four).
-constexpr int kMapLanes = 4;
+// kernels (at N = 8192 a layer is 14 336 window rows: 112 output tiles for 256 CUs; 26.7 ms with one lane, 20.3 ms
+// with four); at long ones a layer's kernels fill the chip and the lanes only close the gaps at kernel boundaries
+// (N = 32 768: 88.6, 86.7, 85.8, 85.2 ms with one to four lanes).
 // The environment variable PROXYKV_MAP_LANES (1 .. kMapLanes) overrides the choice, for measurements.
+constexpr int kMapLanes = 4;
 inline int map_lanes(int64_t window_rows, int distinct_layers) {
-  int lanes = window_rows * kMapLanes <= 131072 ? kMapLanes : 2;
+  (void)window_rows;
+  int lanes = kMapLanes;
   if (const char* env = getenv("PROXYKV_MAP_LANES")) {
     const int v = atoi(env);
     if (v >= 1 && v <= kMapLanes) lanes = v;
