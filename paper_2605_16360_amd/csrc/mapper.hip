@@ -557,6 +557,10 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
   }
   if (n_tiles > 2) fetch(2);
   const int fsw = swz8(l32);
+  // Every load so far (the wave's query fragments among them) has landed before the loop starts.  Without this the
+  // compiler, which cannot tell at the loop head that the query fragments arrived long ago, waits for ALL outstanding
+  // loads in front of the first MFMAs of every tile (the counter is in order), i.e. for the prefetch it has just issued.
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
   for (int t = 0; t < n_tiles; ++t) {
     // every wave has finished tile t-1: its stage takes tile t+2, the registers take tile t+3
