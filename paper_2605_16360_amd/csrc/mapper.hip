@@ -493,6 +493,17 @@ __device__ __forceinline__ float max16_8(const f32x16& a, const f32x16& b) {
   return __builtin_fmaxf(m, b[15]);
 }
 
+// max / sum over the two half-waves without an LDS round trip: the swap leaves the lower half's value in both
+// halves of the first register and the upper half's in both halves of the second
+__device__ __forceinline__ float halves_max(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __builtin_fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float halves_sum(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t* __restrict__ qk,
                                                                    const uint16_t* __restrict__ vt,
                                                                    uint16_t* __restrict__ ao, int64_t T, int n_win) {
@@ -562,6 +573,20 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
   // loads in front of the first MFMAs of every tile (the counter is in order), i.e. for the prefetch it has just issued.
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
+  typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+  const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+  // LDS reads run ahead of their use: the first four K fragments of tile t+1 are read in the tail of tile t (its stage
+  // has been complete since the barrier of tile t), the other four behind the first MFMAs; the V^T fragments of a
+  // 16-key step are read one step ahead and serve both query sub-tiles.
+  auto read_k = [&](const u32x4* st, int ks, f16x8 (&fk)[4]) {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) fk[kk] = as_f16x8(st[(ks * 32 + l32) * 8 + ((kk * 2 + half) ^ fsw)]);
+  };
+  auto read_v = [&](const u32x4* st, int u, f16x8 (&fv)[2]) {
+#pragma unroll
+    for (int ds = 0; ds < 2; ++ds) fv[ds] = as_f16x8(st[512 + (ds * 32 + l32) * 8 + ((u * 2 + half) ^ fsw)]);  // d row, step u
+  };
+  f16x8 fk0[4];
   for (int t = 0; t < n_tiles; ++t) {
     // every wave has finished tile t-1: its stage takes tile t+2, the registers take tile t+3
     __syncthreads();
@@ -570,37 +595,43 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
     const u32x4* st = lds + (t % 3) * 1024;
     const int j0 = t * 64;
     const bool ragged = j0 + 64 > len;
+    if (t == 0) read_k(st, 0, fk0);
 
     // S^T tiles of both query sub-tiles: s[cs][ks] = K[ks] Q[cs]^T
     f32x16 s[2][2];
+    f16x8 fk1[4], fv[2][2];
+    read_k(st, 1, fk1);
+    read_v(st, 0, fv[0]);
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      f16x8 fk[4];
+    for (int cs = 0; cs < 2; ++cs) {
+      f32x16 acc = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) fk[kk] = as_f16x8(st[(ks * 32 + l32) * 8 + ((kk * 2 + half) ^ fsw)]);
-#pragma unroll
-      for (int cs = 0; cs < 2; ++cs) {
-        f32x16 acc = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) acc = mfma_f16_32x32x16(fk[kk], bq[cs][kk], acc);
-        s[cs][ks] = acc;
-      }
+      for (int kk = 0; kk < 4; ++kk) acc = mfma_f16_32x32x16(fk0[kk], bq[cs][kk], acc);
+      s[cs][0] = acc;
     }
 #pragma unroll
     for (int cs = 0; cs < 2; ++cs) {
-      if (ragged) {
+      f32x16 acc = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) acc = mfma_f16_32x32x16(fk1[kk], bq[cs][kk], acc);
+      s[cs][1] = acc;
+    }
+    if (ragged) {
+      const int lim = len - j0 - half * 4;  // element r of tile ks is key j0 + ks*32 + (r>>2)*8 + half*4 + (r&3)
+#pragma unroll
+      for (int cs = 0; cs < 2; ++cs)
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int j = j0 + ks * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-            s[cs][ks][r] = j < len ? s[cs][ks][r] : kNegInf;
-          }
-      }
-      float tmax = max16_8(s[cs][0], s[cs][1]);
-      tmax = __builtin_fmaxf(tmax, swap_halves(tmax)) * c;
-      if (__builtin_amdgcn_ballot_w64(tmax > m_run[cs] + kAttnLazy)) {
-        const float nm = tmax > m_run[cs] + kAttnLazy ? tmax : m_run[cs];
+          for (int r = 0; r < 16; ++r) s[cs][ks][r] = (ks * 32 + (r >> 2) * 8 + (r & 3)) < lim ? s[cs][ks][r] : kNegInf;
+    }
+    float tmax[2];
+#pragma unroll
+    for (int cs = 0; cs < 2; ++cs) tmax[cs] = halves_max(max16_8(s[cs][0], s[cs][1])) * c;
+    if (__builtin_amdgcn_ballot_w64(tmax[0] > m_run[0] + kAttnLazy || tmax[1] > m_run[1] + kAttnLazy)) {
+#pragma unroll
+      for (int cs = 0; cs < 2; ++cs) {
+        const float nm = tmax[cs] > m_run[cs] + kAttnLazy ? tmax[cs] : m_run[cs];
         const float alpha = __builtin_amdgcn_exp2f(m_run[cs] - nm);
         l_run[cs] *= alpha;
 #pragma unroll
@@ -609,31 +640,52 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
           for (int r = 0; r < 16; ++r) o[ds][cs][r] *= alpha;
         m_run[cs] = nm;
       }
-      const float nref = -m_run[cs];
-      float l0 = 0.0f, l1 = 0.0f;
+    }
+    // Four steps of 16 keys.  A wave issues in order, so an MFMA that finds the matrix pipe busy holds back the vector
+    // instructions behind it: the four MFMAs of step u-1 are therefore spread between the vector instructions of
+    // step u (one MFMA, then a quarter of the step's exponentials, conversions and sums), each finding the pipe free.
+    float lsum[2] = {0.0f, 0.0f};
+    f16x8 pb[2][2];  // [step parity][query sub-tile]
+    static_for<5>([&](auto uc) {
+      constexpr int u = decltype(uc)::value;
+      if constexpr (u > 0) {
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
+        for (int ds = 0; ds < 2; ++ds)
 #pragma unroll
-        for (int u2 = 0; u2 < 2; ++u2) {
+          for (int cs = 0; cs < 2; ++cs) o[ds][cs] = mfma_f16_32x32x16(fv[(u - 1) & 1][ds], pb[(u - 1) & 1][cs], o[ds][cs]);
+      }
+      if constexpr (u < 4) {
+        constexpr int ks = u >> 1, u2 = u & 1;
+#pragma unroll
+        for (int cs = 0; cs < 2; ++cs) {
+          const float nref = -m_run[cs];
           f32x8 p;
 #pragma unroll
-          for (int e = 0; e < 8; e += 2) {
-            p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[cs][ks][u2 * 8 + e], c, nref));
-            p[e + 1] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[cs][ks][u2 * 8 + e + 1], c, nref));
-            l0 += p[e];
-            l1 += p[e + 1];
-          }
-          const f16x8 pb = __builtin_convertvector(p, f16x8);
-          const int u = ks * 2 + u2;
+          for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[cs][ks][u2 * 8 + e], c, nref));
+          pb[u & 1][cs] = __builtin_convertvector(p, f16x8);
+          // the row sum takes the probabilities as the second product sees them (rounded to half), two per instruction
 #pragma unroll
-          for (int ds = 0; ds < 2; ++ds) {
-            const f16x8 fv = as_f16x8(st[512 + (ds * 32 + l32) * 8 + ((u * 2 + half) ^ fsw)]);  // V^T: d row, 16-key step u
-            o[ds][cs] = mfma_f16_32x32x16(fv, pb, o[ds][cs]);
+          for (int e = 0; e < 8; e += 2)
+            lsum[cs] = __builtin_amdgcn_fdot2(f16x2{pb[u & 1][cs][e], pb[u & 1][cs][e + 1]}, ones, lsum[cs], false);
+        }
+        // pins the row sums to this step: left alone, the compiler moves all of them behind the last step
+        asm volatile("" : "+v"(lsum[0]), "+v"(lsum[1]));
+        if constexpr (u > 0) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, 12, 0);  // twelve vector instructions
           }
         }
+        // V^T fragments of step u+1 into the buffer that the MFMAs of step u-1 have just released
+        if constexpr (u < 3) read_v(st, u + 1, fv[(u + 1) & 1]);
+      } else {
+        if (t + 1 < n_tiles) read_k(lds + ((t + 1) % 3) * 1024, 0, fk0);
       }
-      l_run[cs] += l0 + l1;
-    }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+#pragma unroll
+    for (int cs = 0; cs < 2; ++cs) l_run[cs] += lsum[cs];
   }
 
   // output: O^T / row sum, through LDS so that every query row is written as 128 contiguous bytes
@@ -641,7 +693,7 @@ __global__ __launch_bounds__(256, 2) void window_attention_kernel(const uint16_t
   uint16_t* ot = reinterpret_cast<uint16_t*>(lds) + wave * (64 * 72);  // [64 queries][64 d + 8 pad] per wave
 #pragma unroll
   for (int cs = 0; cs < 2; ++cs) {
-    const float inv = 1.0f / (l_run[cs] + swap_halves(l_run[cs]));
+    const float inv = 1.0f / halves_sum(l_run[cs]);
 #pragma unroll
     for (int ds = 0; ds < 2; ++ds)
 #pragma unroll
