@@ -77,8 +77,8 @@ int ensure(proxykv_ctx* ctx, DeviceBuffer& b, size_t bytes, hipStream_t stream) 
 }
 
 struct Sizes {
-  size_t neg_lse, x_ws, yhat_ws, h1, z_local, x, xb, qk, vt, ao, hid, zg, kv3, range;
-  size_t mapper() const { return h1 + z_local + x + xb + qk + vt + ao + hid + zg + kv3 + range; }  // one lane's activations
+  size_t neg_lse, x_ws, yhat_ws, h1, x, xb, qk, vt, ao, hid, zg, kv3, range;
+  size_t mapper() const { return h1 + x + xb + qk + vt + ao + hid + zg + kv3 + range; }  // one lane's activations
   size_t total() const { return neg_lse + x_ws + yhat_ws + mapper(); }
 };
 
@@ -92,7 +92,6 @@ Sizes workspace_sizes(const proxykv_config& c, int64_t N, int64_t N_q) {
   s.x_ws = (size_t)c.L_s * c.H_kv * Np * 4;
   s.yhat_ws = (size_t)c.L_l * c.H_l * Np * 4;
   s.h1 = (Np + 2) * (size_t)c.c_mid * 2;
-  s.z_local = Npad * dt * 4;
   s.x = Tp * dt * 4;
   s.xb = Tp * dt * 2;
   s.qk = Tp * 2 * dt * 2;
@@ -130,7 +129,6 @@ int reserve_all(proxykv_ctx* ctx, int64_t N, int64_t N_q, bool score_part, bool 
    for (int lane = 0; lane < lanes; ++lane) {
     pkv::MapperWorkspace& m = ctx->m[lane];
     if ((rc = ensure(ctx, m.h1, s.h1, stream))) return rc;
-    if ((rc = ensure(ctx, m.z_local, s.z_local, stream))) return rc;
     if ((rc = ensure(ctx, m.x, s.x, stream))) return rc;
     if ((rc = ensure(ctx, m.xb, s.xb, stream))) return rc;
     if ((rc = ensure(ctx, m.qk, s.qk, stream))) return rc;
@@ -303,7 +301,7 @@ int proxykv_destroy(proxykv_ctx* ctx) {
   std::vector<DeviceBuffer*> all = {&ctx->weight_blob, &ctx->q_bf16, &ctx->kctx_bf16, &ctx->krec_bf16,
                                     &ctx->neg_lse,     &ctx->x_ws,   &ctx->yhat_ws, &ctx->topk_ws};
   for (pkv::MapperWorkspace& m : ctx->m)
-    for (DeviceBuffer* b : {&m.h1, &m.z_local, &m.x, &m.xb, &m.qk, &m.vt, &m.ao, &m.hid, &m.zg, &m.kv3, &m.range}) all.push_back(b);
+    for (DeviceBuffer* b : {&m.h1, &m.x, &m.xb, &m.qk, &m.vt, &m.ao, &m.hid, &m.zg, &m.kv3, &m.range}) all.push_back(b);
   bool any = ctx->ev_created || ctx->lanes_created;
   for (DeviceBuffer* b : all) any = any || b->ptr;
   if (any) {

@@ -69,7 +69,6 @@ inline int map_lanes(int64_t window_rows, int distinct_layers) {
 
 struct MapperWorkspace {
   DeviceBuffer h1;       // fp16 [(N+2), c_mid]  stem conv1 output with one zero row at each end
-  DeviceBuffer z_local;  // fp32 [N, d_time]
   DeviceBuffer x;        // fp32 [T, d_time]     residual stream over all window rows
   DeviceBuffer xb;       // fp16 [T, d_time]     fp16 copy feeding the GEMMs
   DeviceBuffer qk;       // fp16 [T, 2*d_time]   q and k of the current layer

@@ -142,7 +142,8 @@ __global__ __launch_bounds__(256) void stem_conv1_kernel(const float* __restrict
 // K % 64 == 0, Nn % BN == 0.
 // ------------------------------------------------------------------------------------------
 enum Epilogue {
-  kEpiAffineGeluF32,  // out_f32 = GELU(acc * (p0[n] * *p2) + p1[n])                 (second stem convolution)
+  kEpiGeluPeWin,      // z = GELU(acc * (p0[n] * *p2) + p1[n]) of token m goes, plus the positional row of its place, into the
+                      // row of every window that holds the token: out_f32 and out_h (second stem convolution -> stage-2 input)
   kEpiQkvH,           // columns below 2 * d_time: out_h[m, n] = half(acc + p0[n]), rows ldc apart (q and k);
                       // the others (v): out_v in the transposed, key-permuted layout of the attention kernel
   kEpiBiasReluH,      // out_h = relu(acc + p0[n])
@@ -161,6 +162,8 @@ struct EpiArgs {
   uint16_t* out_h;
   uint16_t* out_v;
   int ldc;  // elements between output rows
+  const float* pe;  // kEpiGeluPeWin: positional table [kWin, d_time]
+  int n_win;        // kEpiGeluPeWin: number of windows
 };
 
 // epilogue stores bypass L2 allocation: the output is not read again by this kernel and would evict W and A rows
@@ -265,7 +268,7 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_kernel(const uint16_t* __rest
     tile_of(it < my_tiles ? it : my_tiles - 1, m0, n0);
     const int n = n0 + wn * 128 + 4 * l32;
     p0 = *reinterpret_cast<const f32x4*>(ep.p0 + n);
-    if constexpr (EPI == kEpiAffineGeluF32) {
+    if constexpr (EPI == kEpiGeluPeWin) {
       p0 *= *ep.p2;
       p1 = *reinterpret_cast<const f32x4*>(ep.p1 + n);
     }
@@ -422,10 +425,25 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_kernel(const uint16_t* __rest
             const int r = qd * 4 + e4;
             f32x4 v = {acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]};
             const size_t o = ob + (size_t)(qd * 8 + e4) * ep.ldc;
-            if constexpr (EPI == kEpiAffineGeluF32) {
+            if constexpr (EPI == kEpiGeluPeWin) {
 #pragma unroll
               for (int e = 0; e < 4; ++e) v[e] = gelu_erf(__builtin_fmaf(v[e], p0[e], p1[e]));
-              PKV_ST(reinterpret_cast<f32x4*>(ep.out_f32 + o), v);
+              // token t sits at place t - 1024 k of window k = min(t / 1024, n_win - 1) and, if that window is not the
+              // first and the token lies in its first half, at place + 1024 of the window before
+              const int t = m0 + wm * 64 + i * 32 + half * 4 + qd * 8 + e4;
+              if (t < M) {
+                const int kq = t / kStride, k1 = kq < ep.n_win ? kq : ep.n_win - 1, p1w = t - k1 * kStride;
+                const size_t o1 = ((size_t)k1 * kWin + p1w) * kDT + n;
+                const f32x4 y1 = v + *reinterpret_cast<const f32x4*>(ep.pe + (size_t)p1w * kDT + n);
+                PKV_ST(reinterpret_cast<f32x4*>(ep.out_f32 + o1), y1);
+                PKV_ST(reinterpret_cast<f16x4*>(ep.out_h + o1), __builtin_convertvector(y1, f16x4));
+                if (k1 >= 1 && kq == k1) {
+                  const size_t o0 = o1 - (size_t)(kWin - kStride) * kDT;  // window k1 - 1, place p1w + 1024
+                  const f32x4 y0 = v + *reinterpret_cast<const f32x4*>(ep.pe + (size_t)(p1w + kStride) * kDT + n);
+                  PKV_ST(reinterpret_cast<f32x4*>(ep.out_f32 + o0), y0);
+                  PKV_ST(reinterpret_cast<f16x4*>(ep.out_h + o0), __builtin_convertvector(y0, f16x4));
+                }
+              }
             } else if constexpr (EPI == kEpiQkvH) {
               PKV_ST(reinterpret_cast<f16x4*>(ep.out_h + o), __builtin_convertvector(v + p0, f16x4));
             } else if constexpr (EPI == kEpiBiasReluH) {
@@ -443,24 +461,6 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_kernel(const uint16_t* __rest
     zero_acc();
     load_bias(s / nk + 1);
   }
-}
-
-// ------------------------------------------------------------------------------------------
-// stage 2 input: window row r = 2048*k + p holds token 1024*k + p;  x = z_local[token] + pe[p]
-// ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void gather_pe_kernel(const float* __restrict__ z_local, const float* __restrict__ pe,
-                                                         float* __restrict__ x, uint16_t* __restrict__ xb, int64_t T) {
-  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;  // one float4 each
-  if (gid >= T * (kDT / 4)) return;
-  const int64_t r = gid / (kDT / 4);
-  const int c4 = (int)(gid % (kDT / 4));
-  const int64_t k = r / kWin;
-  const int p = (int)(r % kWin);
-  const f32x4 a = *reinterpret_cast<const f32x4*>(z_local + (size_t)(k * kStride + p) * kDT + c4 * 4);
-  const f32x4 b = *reinterpret_cast<const f32x4*>(pe + (size_t)p * kDT + c4 * 4);
-  const f32x4 s = a + b;
-  *reinterpret_cast<f32x4*>(x + (size_t)r * kDT + c4 * 4) = s;
-  *reinterpret_cast<f16x4*>(xb + (size_t)r * kDT + c4 * 4) = __builtin_convertvector(s, f16x4);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -845,7 +845,6 @@ hipError_t mapper_layer(proxykv_ctx* ctx, MapperWorkspace& m, const float* xl, i
   int64_t n_win, T;
   window_plan(N, c.win, c.stride, &n_win, &T);
   uint16_t* h1 = (uint16_t*)m.h1.ptr;
-  float* z_local = (float*)m.z_local.ptr;
   float* x = (float*)m.x.ptr;
   uint16_t* xb = (uint16_t*)m.xb.ptr;
   uint16_t* qk = (uint16_t*)m.qk.ptr;
@@ -855,7 +854,6 @@ hipError_t mapper_layer(proxykv_ctx* ctx, MapperWorkspace& m, const float* xl, i
   uint16_t* zg = (uint16_t*)m.zg.ptr;
   float* kv3 = (float*)m.kv3.ptr;
   uint32_t* range = (uint32_t*)m.range.ptr;
-  const unsigned ew_blocks_T = (unsigned)((T * (kDT / 4) + 255) / 256);
   const unsigned ew_blocks_N = (unsigned)((N * (kDT / 4) + 255) / 256);
 
   // stage 1
@@ -874,13 +872,14 @@ hipError_t mapper_layer(proxykv_ctx* ctx, MapperWorkspace& m, const float* xl, i
   e2.p0 = w.bn2_scale;
   e2.p1 = w.bn2_shift;
   e2.p2 = reinterpret_cast<const float*>(range) + 2;
-  e2.out_f32 = z_local;
+  e2.out_f32 = x;
+  e2.out_h = xb;
   e2.ldc = kDT;
-  PKV_TRY((launch_gemm<kEpiAffineGeluF32, 256, 256>(h1, c.c_mid, w.conv2_w, N, kDT, 3 * c.c_mid, e2, n_cu, stream)));
+  e2.pe = w.pe;
+  e2.n_win = (int)n_win;
+  PKV_TRY((launch_gemm<kEpiGeluPeWin, 256, 256>(h1, c.c_mid, w.conv2_w, N, kDT, 3 * c.c_mid, e2, n_cu, stream)));
 
-  // stage 2
-  gather_pe_kernel<<<ew_blocks_T, 256, 0, stream>>>(z_local, w.pe, x, xb, T);
-  PKV_TRY(hipGetLastError());
+  // stage 2 (the stem's epilogue has written its input rows)
   for (int li = 0; li < c.n_enc_layers; ++li) {
     const EncoderLayerWeights& e = w.enc[li];
     EpiArgs eq = {};
