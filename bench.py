@@ -116,6 +116,9 @@ def main():
     ap.add_argument("--overlap", action="store_true",
                     help="also run one prune next to a stand-in prefill load on a second stream and report both")
     ap.add_argument("--extras", action="store_true", help="also time proxykv_compact_inplace and proxykv_mask once")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="also time the vendor library's fp16 matrix product (torch.matmul, no bias, no epilogue) on the "
+                         "shapes of the encoder's four linear maps: a reference for the mapper's own GEMM kernels")
     ap.add_argument("--reduce", choices=("max", "sum"), default="max",
                     help="reduction over the query axis: max (the headline path) or sum (the form Sec. 3 prints); "
                          "with sum the stage reported as score_colmax is the column-sum kernel")
@@ -268,6 +271,30 @@ def main():
                           "both_ms_one_after_the_other": t_prune_alone + t_gemm_alone,
                           "both_ms_together": t_both}
         del a, b, cbuf
+    if args.vendor_gemm:
+        # window rows of one proxy layer x the encoder's four linear maps (Sec. 4.1): what the vendor library needs for the
+        # bare products that the mapper's GEMM kernels compute together with their epilogues
+        win, stride = 2048, 1024
+        n_win = 1 if case.N <= win else -((-(case.N - win)) // stride) + 1
+        rows = sum(min(k * stride + win, case.N) - k * stride for k in range(n_win))
+        ref = {}
+        for name, n_out, k_in in (("qkv", 1536, 512), ("ffn1", 2048, 512), ("out_proj", 512, 512), ("ffn2", 512, 2048)):
+            a = torch.randn(rows, k_in, device=dev, dtype=torch.float16)
+            w = torch.randn(n_out, k_in, device=dev, dtype=torch.float16)
+            o = torch.empty(rows, n_out, device=dev, dtype=torch.float16)
+            for _ in range(5):
+                torch.matmul(a, w.t(), out=o)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(50):
+                torch.matmul(a, w.t(), out=o)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / 50 * 1e3
+            ref[name] = {"rows": rows, "n": n_out, "k": k_in, "us": us, "tflops": 2 * rows * n_out * k_in / us / 1e6}
+            del a, w, o
+        out["vendor_gemm"] = ref
     if args.extras:
         # entry points outside the timed path: the cache compacted where it lies, and the byte mask
         k_ip, v_ip = k_t.clone(), v_t.clone()
