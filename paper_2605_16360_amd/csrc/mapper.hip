@@ -126,7 +126,8 @@ __global__ __launch_bounds__(256) void stem_conv1_kernel(const float* __restrict
 // tile), so a lane holds four adjacent columns in its four tiles and every store instruction writes
 // whole 256-byte (fp16) or 512-byte (fp32) row segments, 8 or 16 bytes per lane.  Output (and residual)
 // buffers have their row count padded to a multiple of 256, so the epilogue has no row predicate; rows
-// at and past M are written with values that nobody reads.
+// at and past M are written with values that nobody reads (the stem's epilogue, which writes a token's row into
+// the windows that hold it, skips them instead).
 //
 // The K steps of all tiles of a workgroup form one stream: two LDS stages (64 or 80 KB each) and ONE barrier
 // per step.  A step is four phases of 8 MFMAs; the fragments of phase kk+1 are read from LDS between
