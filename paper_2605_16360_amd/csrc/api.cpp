@@ -77,8 +77,8 @@ int ensure(proxykv_ctx* ctx, DeviceBuffer& b, size_t bytes, hipStream_t stream) 
 }
 
 struct Sizes {
-  size_t neg_lse, x_ws, yhat_ws, h1, x, xb, qk, vt, ao, hid, zg, kv3, range;
-  size_t mapper() const { return h1 + x + xb + qk + vt + ao + hid + zg + kv3 + range; }  // one lane's activations
+  size_t neg_lse, x_ws, yhat_ws, h1, x, xb, qk, vt, ao, hid, zg, s3, range;
+  size_t mapper() const { return h1 + x + xb + qk + vt + ao + hid + zg + s3 + range; }  // one lane's activations
   size_t total() const { return neg_lse + x_ws + yhat_ws + mapper(); }
 };
 
@@ -99,7 +99,7 @@ Sizes workspace_sizes(const proxykv_config& c, int64_t N, int64_t N_q) {
   s.ao = Tp * dt * 2;
   s.hid = Tp * (size_t)c.d_ffn * 2;
   s.zg = Np * dt * 2;
-  s.kv3 = Npad * (size_t)pkv::kv3_stride(c) * 4;
+  s.s3 = Npad * (size_t)(c.H_l + 1) * (size_t)c.H_kv * 4;
   s.range = 256;
   return s;
 }
@@ -136,7 +136,7 @@ int reserve_all(proxykv_ctx* ctx, int64_t N, int64_t N_q, bool score_part, bool 
     if ((rc = ensure(ctx, m.ao, s.ao, stream))) return rc;
     if ((rc = ensure(ctx, m.hid, s.hid, stream))) return rc;
     if ((rc = ensure(ctx, m.zg, s.zg, stream))) return rc;
-    if ((rc = ensure(ctx, m.kv3, s.kv3, stream))) return rc;
+    if ((rc = ensure(ctx, m.s3, s.s3, stream))) return rc;
     if ((rc = ensure(ctx, m.range, s.range, stream))) return rc;
    }
   }
@@ -301,7 +301,7 @@ int proxykv_destroy(proxykv_ctx* ctx) {
   std::vector<DeviceBuffer*> all = {&ctx->weight_blob, &ctx->q_bf16, &ctx->kctx_bf16, &ctx->krec_bf16,
                                     &ctx->neg_lse,     &ctx->x_ws,   &ctx->yhat_ws, &ctx->topk_ws};
   for (pkv::MapperWorkspace& m : ctx->m)
-    for (DeviceBuffer* b : {&m.h1, &m.x, &m.xb, &m.qk, &m.vt, &m.ao, &m.hid, &m.zg, &m.kv3, &m.range}) all.push_back(b);
+    for (DeviceBuffer* b : {&m.h1, &m.x, &m.xb, &m.qk, &m.vt, &m.ao, &m.hid, &m.zg, &m.s3, &m.range}) all.push_back(b);
   bool any = ctx->ev_created || ctx->lanes_created;
   for (DeviceBuffer* b : all) any = any || b->ptr;
   if (any) {

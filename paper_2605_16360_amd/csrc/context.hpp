@@ -76,7 +76,7 @@ struct MapperWorkspace {
   DeviceBuffer ao;       // fp16 [T, d_time]     attention output
   DeviceBuffer hid;      // fp16 [T, d_ffn]
   DeviceBuffer zg;       // fp16 [N, d_time]     overlap-averaged encoder output
-  DeviceBuffer kv3;      // fp32 [N, kv3_stride]  stage-3 keys then values of every slot, then padding
+  DeviceBuffer s3;       // fp32 [N, (H_l + 1) * H_s]  stage 3: per token the H_l x H_s logits, then <w_o, V[s]> of every slot
   DeviceBuffer range;    // 3 words: largest |score| of the layer (bits), 2^-s and 2^s of the stem's range exponent
 };
 

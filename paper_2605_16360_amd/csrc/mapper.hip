@@ -7,7 +7,8 @@
 //                                 with the same epilogue; all sliding windows of the layer are batched along the
 //                                 GEMM M axis
 //            overlap averaging    overlap_avg_kernel
-//   stage 3  head-axis attention  K/V projection GEMM + stage3_kernel (per token, fp32 ALU)
+//   stage 3  head-axis attention  K/V projection GEMM (inner products with queries / output weights in its epilogue)
+//                                  + stage3_kernel (softmax over the slots per token and head, fp32 ALU)
 // Matrix products take IEEE half (fp16) operands and accumulate in fp32 on v_mfma_f32_32x32x16_f16; the
 // residual stream, normalisation, softmax and GELU are fp32.
 #include "common.hpp"
@@ -148,7 +149,8 @@ enum Epilogue {
   kEpiQkvH,           // columns below 2 * d_time: out_h[m, n] = half(acc + p0[n]), rows ldc apart (q and k);
                       // the others (v): out_v in the transposed, key-permuted layout of the attention kernel
   kEpiBiasReluH,      // out_h = relu(acc + p0[n])
-  kEpiBiasF32,        // out_f32 = acc + p0[n]
+  kEpiStage3,         // columns = stage-3 key and value slots of 64: per token and slot the inner products of
+                      // acc + p0 with the learned queries (p1, n_head of them, times 1/8) or with the output weights (g)
   kEpiResLn           // BN = 512: y = LayerNorm(res[m, :] + acc + p0) * g + b -> out_f32 (may be res) and out_h
 };
 
@@ -165,6 +167,7 @@ struct EpiArgs {
   int ldc;  // elements between output rows
   const float* pe;  // kEpiGeluPeWin: positional table [kWin, d_time]
   int n_win;        // kEpiGeluPeWin: number of windows
+  int n_slot, n_head;  // kEpiStage3: slots H_s (keys in columns [0, 64 H_s), values in [64 H_s, 128 H_s)) and queries H_l
 };
 
 // epilogue stores bypass L2 allocation: the output is not read again by this kernel and would evict W and A rows
@@ -189,6 +192,22 @@ __device__ __forceinline__ float reduce16_over_lanes(float (&v)[16], int l32) {
     }
   });
   return v[0] + __shfl_xor(v[0], 1, 64);
+}
+
+// Sum of v[0..15] over the 16 lanes that share the upper bits of the lane number, sixteen sums at once, by the same
+// halving exchange: afterwards lane j (lane & 15) holds the sum of v[j].  15 exchanges.
+__device__ __forceinline__ float reduce16_over_16_lanes(float (&v)[16], int lane) {
+  static_for<4>([&](auto sc) {
+    constexpr int step = decltype(sc)::value, n = 8 >> step, mask = 8 >> step;
+    const bool up = (lane & mask) != 0;
+#pragma unroll
+    for (int j = 0; j < n; ++j) {
+      const float send = up ? v[j] : v[j + n];
+      const float keep = up ? v[j + n] : v[j];
+      v[j] = keep + __shfl_xor(send, mask, 64);
+    }
+  });
+  return v[0];
 }
 
 template <int EPI, int BM, int BN>
@@ -396,6 +415,35 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_kernel(const uint16_t* __rest
         }
       }
       __syncthreads();  // the stage may be overwritten again
+    } else if constexpr (EPI == kEpiStage3) {
+      // The 64 columns of a slot sit in 16 lanes (four columns each).  Per 32-row block: the lane's share of every row's
+      // inner product with one coefficient vector, sixteen rows reduced over the 16 lanes at once, lane j keeps row j of
+      // the sixteen that its half-wave holds.  Key slots take the n_head queries in turn, value slots the output weights.
+      const int col = n0 + wn * 128 + (l32 >> 4) * 64;  // first column of the lane group's slot
+      const int slot = col >> 6, e0 = (l32 & 15) * 4;
+      const bool is_k = slot < ep.n_slot, is_v = !is_k && slot < 2 * ep.n_slot;
+      const int sv = is_k ? slot : slot - ep.n_slot;
+      const int j16 = l32 & 15;
+      const int n_pass = ep.n_head;  // uniform; value slots use pass 0 only
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int row = m0 + wm * 64 + i * 32 + (j16 >> 2) * 8 + half * 4 + (j16 & 3);  // the row this lane ends up with
+        float* orow = ep.out_f32 + (size_t)row * ep.ldc;
+        for (int h = 0; h < n_pass; ++h) {
+          const float* cf = is_k ? ep.p1 + (size_t)h * 64 + e0 : ep.g + e0;
+          const f32x4 c4 = *reinterpret_cast<const f32x4*>(cf);
+          float part[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            part[r] = (acc[i][0][r] + p0[0]) * c4[0] + (acc[i][1][r] + p0[1]) * c4[1] + (acc[i][2][r] + p0[2]) * c4[2] +
+                      (acc[i][3][r] + p0[3]) * c4[3];
+          const float tot = reduce16_over_16_lanes(part, l32);
+          if (row < M) {
+            if (is_k) orow[h * ep.n_slot + sv] = tot * 0.125f;
+            else if (is_v && h == 0) orow[ep.n_head * ep.n_slot + sv] = tot;
+          }
+        }
+      }
     } else {
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
@@ -452,8 +500,6 @@ __global__ __launch_bounds__(512, 1) void gemm_f16_kernel(const uint16_t* __rest
 #pragma unroll
               for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaxf(v[e], 0.0f);
               PKV_ST(reinterpret_cast<f16x4*>(ep.out_h + o), __builtin_convertvector(v, f16x4));
-            } else {
-              PKV_ST(reinterpret_cast<f32x4*>(ep.out_f32 + o), v + p0);
             }
           }
         }
@@ -742,65 +788,27 @@ __global__ __launch_bounds__(256) void overlap_avg_kernel(const float* __restric
 }
 
 // ------------------------------------------------------------------------------------------
-// stage 3 per token (Eq. 3): kv3[t] = [K slots | V slots] (H_s x 64 each, biases included);
-// yhat[ll, h, t] = sum_s softmax_s(<Q_l[h], K[s]> / 8) * <w_o, V[s]> + b_o for every paired target layer ll.
+// stage 3 per token (Eq. 3), after the K/V projection GEMM whose epilogue has already taken the inner products:
+// s3[t] = [ <Q_l[h], K[s]> / 8 for h < H_l, s < H_s | <w_o, V[s]> for s < H_s ];
+// yhat[ll, h, t] = sum_s softmax_s(logit[h][s]) * u[s] + b_o for every paired target layer ll.
 // Block = 256 threads = (256 / H_l) tokens x H_l target heads, token index fastest.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void stage3_kernel(const float* __restrict__ kv3, const float* __restrict__ queries,
-                                                      const float* __restrict__ w_o, float b_o, float* __restrict__ yhat,
-                                                      int64_t N, int H_s, int H_l, int row_f, int ll_lo, int ll_hi) {
-  __shared__ float u_lds[256 * kMaxHs / 1];  // [token][slot], at most 256 tokens... sized for H_l = 1
+__global__ __launch_bounds__(256) void stage3_kernel(const float* __restrict__ s3, float b_o, float* __restrict__ yhat,
+                                                      int64_t N, int H_s, int H_l, int ll_lo, int ll_hi) {
   const int tok_per_block = 256 / H_l;
-  const int64_t t0 = (int64_t)blockIdx.x * tok_per_block;
-  // phase 1: u[token][s] = <w_o, V[s]>
-  for (int i = threadIdx.x; i < tok_per_block * H_s; i += 256) {
-    const int tt = i % tok_per_block, s = i / tok_per_block;
-    const int64_t t = t0 + tt;
-    float acc = 0.0f;
-    if (t < N) {
-      const float* v = kv3 + (size_t)t * row_f + (H_s + s) * 64;
-#pragma unroll
-      for (int e = 0; e < 64; e += 4) {
-        const f32x4 vv = *reinterpret_cast<const f32x4*>(v + e);
-        const f32x4 ww = *reinterpret_cast<const f32x4*>(w_o + e);
-        acc += vv[0] * ww[0] + vv[1] * ww[1] + vv[2] * ww[2] + vv[3] * ww[3];
-      }
-    }
-    u_lds[tt * kMaxHs + s] = acc;
-  }
-  __syncthreads();
   const int tt = threadIdx.x % tok_per_block, h = threadIdx.x / tok_per_block;
-  const int64_t t = t0 + tt;
+  const int64_t t = (int64_t)blockIdx.x * tok_per_block + tt;
   if (h >= H_l || t >= N) return;
-  float logit[kMaxHs];
-#pragma unroll
-  for (int s = 0; s < kMaxHs; ++s) logit[s] = kNegInf;
-  const float* qh = queries + (size_t)h * 64;
-#pragma unroll
-  for (int s = 0; s < kMaxHs; ++s) {
-    if (s < H_s) {
-      const float* k = kv3 + (size_t)t * row_f + s * 64;
-      float acc = 0.0f;
-#pragma unroll
-      for (int e = 0; e < 64; e += 4) {
-        const f32x4 kk = *reinterpret_cast<const f32x4*>(k + e);
-        const f32x4 qq = *reinterpret_cast<const f32x4*>(qh + e);
-        acc += kk[0] * qq[0] + kk[1] * qq[1] + kk[2] * qq[2] + kk[3] * qq[3];
-      }
-      logit[s] = acc * 0.125f;
-    }
-  }
+  const float* row = s3 + (size_t)t * ((H_l + 1) * H_s);
+  const float* lg = row + h * H_s;
+  const float* u = row + H_l * H_s;
   float mx = kNegInf;
-#pragma unroll
-  for (int s = 0; s < kMaxHs; ++s) mx = __builtin_fmaxf(mx, logit[s]);
+  for (int s = 0; s < H_s; ++s) mx = __builtin_fmaxf(mx, lg[s]);
   float den = 0.0f, num = 0.0f;
-#pragma unroll
-  for (int s = 0; s < kMaxHs; ++s) {
-    if (s < H_s) {
-      const float e = __expf(logit[s] - mx);
-      den += e;
-      num += e * u_lds[tt * kMaxHs + s];
-    }
+  for (int s = 0; s < H_s; ++s) {
+    const float e = __expf(lg[s] - mx);
+    den += e;
+    num += e * u[s];
   }
   const float y = num / den + b_o;
   for (int ll = ll_lo; ll < ll_hi; ++ll) yhat[((size_t)ll * H_l + h) * N + t] = y;
@@ -853,7 +861,7 @@ hipError_t mapper_layer(proxykv_ctx* ctx, MapperWorkspace& m, const float* xl, i
   uint16_t* ao = (uint16_t*)m.ao.ptr;
   uint16_t* hid = (uint16_t*)m.hid.ptr;
   uint16_t* zg = (uint16_t*)m.zg.ptr;
-  float* kv3 = (float*)m.kv3.ptr;
+  float* s3 = (float*)m.s3.ptr;
   uint32_t* range = (uint32_t*)m.range.ptr;
   const unsigned ew_blocks_N = (unsigned)((N * (kDT / 4) + 255) / 256);
 
@@ -918,12 +926,16 @@ hipError_t mapper_layer(proxykv_ctx* ctx, MapperWorkspace& m, const float* xl, i
   const int nkv = kv3_stride(c);
   EpiArgs e3 = {};
   e3.p0 = w.kv_b;
-  e3.out_f32 = kv3;
-  e3.ldc = nkv;
-  PKV_TRY((launch_gemm<kEpiBiasF32, 256, 256>(zg, kDT, w.kv_w, N, nkv, kDT, e3, n_cu, stream)));
+  e3.p1 = w.queries;
+  e3.g = w.out_w;
+  e3.out_f32 = s3;
+  e3.ldc = (c.H_l + 1) * c.H_kv;
+  e3.n_slot = c.H_kv;
+  e3.n_head = c.H_l;
+  PKV_TRY((launch_gemm<kEpiStage3, 256, 256>(zg, kDT, w.kv_w, N, nkv, kDT, e3, n_cu, stream)));
   const int tok_per_block = 256 / c.H_l;
-  stage3_kernel<<<(unsigned)((N + tok_per_block - 1) / tok_per_block), 256, 0, stream>>>(kv3, w.queries, w.out_w, w.out_b, yhat, N,
-                                                                                        c.H_kv, c.H_l, nkv, ll, ll_hi);
+  stage3_kernel<<<(unsigned)((N + tok_per_block - 1) / tok_per_block), 256, 0, stream>>>(s3, w.out_b, yhat, N, c.H_kv, c.H_l, ll,
+                                                                                        ll_hi);
   return hipGetLastError();
 }
 
